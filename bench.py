@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the SBP matmul + boxing hot path on one MI355X.
+
+One step = one pass of the whole path over the Megatron-style MLP workload (k = 8 logical
+devices as 8 shard sets in one GPU's HBM):
+
+    H  = gelu(X W1)     X [8192,4096] bf16 B,  W1 [4096,16384] bf16 S(1)  -> H S(1) bf16
+    Y  = H W2           W2 [16384,4096] bf16 S(0)                         -> Y P(sum), 8 fp32 partials
+    Yb = boxing(Y)      P(sum) -> B (all-reduce): 8 partials -> 8 identical fp32 copies
+
+Inputs are seeded synthetic tensors, resident in HBM before the timed region.  Prints ONE JSON line.
+`value` is the matmul work of a step (2.199 TFLOP) divided by the time of the whole step (boxing
+included); the per-kernel figures are in "kernels", "roofline" (dominant kernel) and
+"roofline_boxing".  The CPU oracle is timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak, TFLOP/s
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak, GB/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--cpu-rows", type=int, default=512, help="token rows in the oracle's sample")
+    ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the k logical devices are k shard buffers in one HBM); "
+              "--gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2110_15032_amd as sbp
+    import workloads as wl
+    from workloads import CONFIGS
+
+    sbp.lib()   # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = CONFIGS["mlp"]
+    k = cfg["k"]
+    T, D = cfg["X"]["shape"]          # 8192 tokens, 4096 model width
+    F = cfg["W1"]["shape"][1]         # 16384 hidden width
+    seed = wl.SEED_BASE
+
+    def bf16_dev(spec, rows=None, cols=None):
+        x = wl.normal(seed, spec["id"], spec["shape"], spec["dist"][1], rows, cols, dtype=np.float32)
+        return torch.from_numpy(wl.to_bf16_bits(x).view(np.int16)).to(dev)
+
+    t0 = time.time()
+    x_full = bf16_dev(cfg["X"])
+    x_sh = [x_full] + [x_full.clone() for _ in range(k - 1)]                     # B: k physical copies
+    w1_sh = [bf16_dev(cfg["W1"], cols=np.arange(*wl.split_range(F, k, i))) for i in range(k)]   # [4096, 2048]
+    w2_sh = [bf16_dev(cfg["W2"], rows=np.arange(*wl.split_range(F, k, i))) for i in range(k)]   # [2048, 4096]
+    h_sh = [torch.empty((T, F // k), dtype=torch.int16, device=dev) for _ in range(k)]
+    y_sh = [torch.empty((T, D), dtype=torch.float32, device=dev) for _ in range(k)]
+    yb_sh = [torch.empty((T, D), dtype=torch.float32, device=dev) for _ in range(k)]
+    gen_s = time.time() - t0
+
+    X = sbp.SbpTensor(x_sh, T, D, sbp.BF16)
+    W1 = sbp.SbpTensor(w1_sh, D, F, sbp.BF16)
+    W2 = sbp.SbpTensor(w2_sh, F, D, sbp.BF16)
+    H = sbp.SbpTensor(h_sh, T, F, sbp.BF16)
+    Y = sbp.SbpTensor(y_sh, T, D, sbp.F32)
+    Yb = sbp.SbpTensor(yb_sh, T, D, sbp.F32)
+    stream = torch.cuda.current_stream()
+    sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, args.variant)
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        sbp.sbp_matmul_ex(X, sbp.B, W1, sbp.S(1), H, sbp.S(1), k, stream, sbp.EPI_GELU)
+        if ev:
+            ev[1].record(stream)
+        sbp.sbp_matmul(H, sbp.S(1), W2, sbp.S(0), Y, sbp.P_SUM, k, stream)
+        if ev:
+            ev[2].record(stream)
+        sbp.sbp_boxing(Y, sbp.P_SUM, Yb, sbp.B, k, stream)
+        if ev:
+            ev[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps, HIP events on the launch stream around every kernel
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_begin) * 1e3
+    ms_per_step = wall_ms / args.steps
+    k_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i in range(3)]
+
+    flops_gemm = 2.0 * T * D * F                      # per GEMM, summed over the 8 shards
+    bytes_box = 2.0 * k * T * D * 4                   # P->B: read k partials, write k copies
+    gemm1_tf = flops_gemm / (k_ms[0] * 1e-3) / 1e12
+    gemm2_tf = flops_gemm / (k_ms[1] * 1e-3) / 1e12
+    box_gbps = bytes_box / (k_ms[2] * 1e-3) / 1e9
+    value = 2.0 * flops_gemm / (ms_per_step * 1e-3) / 1e12
+    dom = 0 if k_ms[0] >= k_ms[1] else 1
+    dom_name = ["sbp_matmul (B,S1)->S1 bf16 + GeLU", "sbp_matmul (S1,S0)->P(sum) fp32 partials"][dom]
+    dom_tf = [gemm1_tf, gemm2_tf][dom]
+
+    out = {
+        "metric": "SBP matmul TFLOP/s (% MFMA peak) + boxing GB/s (% HBM peak), k=8",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "Megatron-style MLP block, k=8: X[8192,4096] bf16 B; W1[4096,16384] S(1) -> H S(1) "
+                               "(GeLU); W2[16384,4096] S(0) -> Y P(sum); boxing P->B of 8 fp32 8192x4096 partials",
+                   "k": k, "gemm_variant": args.variant},
+        "kernels": {
+            "gemm1_gelu_ms": round(k_ms[0], 4), "gemm1_tflops": round(gemm1_tf, 2),
+            "gemm2_psum_ms": round(k_ms[1], 4), "gemm2_tflops": round(gemm2_tf, 2),
+            "boxing_p2b_ms": round(k_ms[2], 4), "boxing_gbps": round(box_gbps, 1),
+            "matmul_pct_mfma_peak": round(100 * 2 * flops_gemm / ((k_ms[0] + k_ms[1]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+            "boxing_pct_hbm_peak": round(100 * box_gbps / PEAK_HBM_GBPS, 2),
+            "input_gen_s": round(gen_s, 2),
+        },
+        "roofline": {"bound": "mfma", "kernel": dom_name, "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "roofline_boxing": {"bound": "hbm", "kernel": "sbp_boxing P(sum)->B", "achieved": round(box_gbps, 1),
+                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(box_gbps / PEAK_HBM_GBPS, 4),
+                            "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, k, args.cpu_rows, seed)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, k, rows, seed):
+    """The oracle, as it stands, on the first `rows` tokens of the same workload: per-shard GEMM1,
+    GeLU, bf16 rounding, per-shard GEMM2 partials, P(sum)->B.  Same algorithmic FLOP count per
+    token as the GPU step."""
+    import numpy as np
+
+    import oracle as orc
+    import workloads as wl
+
+    T, D = cfg["X"]["shape"]
+    F = cfg["W1"]["shape"][1]
+    r = np.arange(rows)
+    Xs = orc.bf16_to_f64(wl.to_bf16_bits(wl.normal(seed, cfg["X"]["id"], (T, D), 1.0, rows=r)))
+    W1 = orc.bf16_to_f64(wl.to_bf16_bits(wl.normal(seed, cfg["W1"]["id"], (D, F), cfg["W1"]["dist"][1])))
+    W2 = orc.bf16_to_f64(wl.to_bf16_bits(wl.normal(seed, cfg["W2"]["id"], (F, D), cfg["W2"]["dist"][1])))
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t0 = time.perf_counter()
+    Hs, s_h = orc.matmul_sbp(orc.scatter(Xs, orc.B, k), orc.B, orc.scatter(W1, orc.S1, k), orc.S1)
+    Hs = [orc.bf16_to_f64(orc.bf16_round(orc.gelu(h))) for h in Hs]
+    Ys, s_y = orc.matmul_sbp(Hs, orc.S1, orc.scatter(W2, orc.S0, k), orc.S0)
+    Yb = orc.boxing(Ys, s_y, orc.B, k)
+    dt = time.perf_counter() - t0
+    flops = 2 * 2.0 * rows * D * F
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {rows} of {T} tokens through the whole step (GEMM1+GeLU, GEMM2 partials, P->B), "
+                      f"{flops / 1e9:.1f} GFLOP in {dt:.2f} s",
+            "checksum": float(np.sum(Yb[0]))}
+
+
+if __name__ == "__main__":
+    main()

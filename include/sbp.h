@@ -1,0 +1,159 @@
+/*
+ * sbp.h -- C ABI of the MI355X (gfx950) SBP matmul + boxing library.
+ *
+ * Vocabulary (OneFlow paper, arXiv 2110.15032, Sec. 3.1): a *global* (logical)
+ * tensor placed on k devices is represented by k *local* tensors, related by an
+ * SBP signature:
+ *     split(a)       S(a): locals are a balanced split of the global along axis a
+ *     broadcast      B   : every local is an exact copy of the global
+ *     partial-value  P(op): locals have the global shape, global = elementwise
+ *                           op (sum | max) over all locals
+ * Here the k devices are k shard buffers in ONE GPU's memory.
+ *
+ * Conventions for every function:
+ *   - extern "C"; returns an int32 status: SBP_OK (0) or a negative SBP_ERR_*.
+ *     On any error nothing has been enqueued.  Nothing throws.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
+ *     is enqueued on it; no call synchronises, none allocates device memory.
+ *   - sbp_tensor_t.shard is a HOST array of k DEVICE pointers.  The caller owns
+ *     the array and every buffer; the library reads the array during the call
+ *     only.  Every device pointer must be 16-byte aligned.
+ *   - Local tensors are dense and row-major.  Shard i's local shape follows
+ *     from (rows, cols, sbp, k, i): S(0) -> rows split, S(1) -> cols split,
+ *     B / P -> full shape.  The split is the balanced one: floor(n/k) indices
+ *     each, the first (n mod k) shards one more (the paper only says
+ *     "balanced"; this is the reading taken).
+ *   - trans = 1: shard i stores the TRANSPOSE of logical local tensor i
+ *     (row-major [local_cols, local_rows]).  rows / cols / sbp always describe
+ *     the logical tensor.
+ *   - Output buffers must not overlap input buffers (SBP_ERR_ALIAS).  A B input
+ *     may name the same buffer k times (one physical copy standing for k).
+ *   - Boxing is never implicit: sbp_matmul writes Y under exactly the signature
+ *     Table 1 gives; converting it is a separate sbp_boxing call, as in the
+ *     paper where the compiler or to_global() inserts the boxing op (Sec. 3.2,
+ *     Sec. 3.4).
+ */
+#ifndef SBP_MI355X_H
+#define SBP_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- SBP signatures -------------------------------------------------------*/
+typedef int32_t sbp_t;
+#define SBP_S(axis) ((sbp_t)(axis)) /* axis = 0 | 1 */
+#define SBP_B       ((sbp_t)-1)
+#define SBP_P_SUM   ((sbp_t)-2)
+#define SBP_P_MAX   ((sbp_t)-3)
+#define SBP_AUTO    ((sbp_t)-100)   /* sbp_matmul only: "whatever Table 1 says" */
+
+/* ---- element types --------------------------------------------------------*/
+enum { SBP_F32 = 0, SBP_BF16 = 1 };
+
+/* ---- status codes ---------------------------------------------------------*/
+enum {
+    SBP_OK = 0,
+    SBP_ERR_NULL = -1,        /* null descriptor, shard array or shard pointer          */
+    SBP_ERR_K = -2,           /* k < 1 or k > SBP_MAX_K                                  */
+    SBP_ERR_SHAPE = -3,       /* negative extent, or operand shapes do not compose       */
+    SBP_ERR_DTYPE = -4,       /* unknown dtype, or dtype not allowed in that position    */
+    SBP_ERR_AXIS = -5,        /* not a signature (split axis other than 0 / 1, ...)      */
+    SBP_ERR_SIGNATURE = -6,   /* (sbp_x, sbp_w) not in Table 1, or sbp_y != the deduced  */
+    SBP_ERR_ALIAS = -7,       /* an output buffer overlaps an input or another output    */
+    SBP_ERR_ALIGN = -8,       /* a device pointer is not 16-byte aligned                 */
+    SBP_ERR_UNSUPPORTED = -9, /* a valid request this build has no kernel for            */
+    SBP_ERR_LAUNCH = -10      /* the HIP runtime refused the launch                      */
+};
+#define SBP_MAX_K 64
+
+/* ---- a global tensor and its k local tensors ------------------------------*/
+typedef struct sbp_tensor {
+    void* const* shard; /* host array [k] of device pointers                          */
+    int64_t rows, cols; /* GLOBAL shape; vectors are [n, 1]                           */
+    int32_t dtype;      /* SBP_F32 | SBP_BF16                                         */
+    int32_t trans;      /* 0: shards hold the local tensor; 1: its transpose          */
+} sbp_tensor_t;
+
+/* ---- epilogues of sbp_matmul_ex -------------------------------------------*/
+enum {
+    SBP_EPI_NONE = 0,
+    SBP_EPI_GELU = 1    /* y <- gelu(acc), exact erf form, evaluated in fp32 on the accumulator
+                           before the single rounding to y's dtype.  Elementwise, so only allowed
+                           when Y is S or B (an elementwise nonlinearity of a P(sum) partial is
+                           not the nonlinearity of the global value).                           */
+};
+
+/* Table 1 of the paper (Sec. 3.1): the signature of Y = XW from those of X and W.
+ * Valid pairs: (S0,B)->S0, (B,S1)->S1, (S1,S0)->P(sum), (P(sum),B)->P(sum),
+ * (B,P(sum))->P(sum), (B,B)->B.  Host only.  SBP_ERR_SIGNATURE for any other pair. */
+int32_t sbp_infer_matmul(sbp_t sbp_x, sbp_t sbp_w, sbp_t* sbp_y);
+
+/* Local shape of shard i (Sec. 3.1, balanced split).  Host only. */
+int32_t sbp_local_shape(int64_t rows, int64_t cols, sbp_t sbp, int32_t k, int32_t i,
+                        int64_t* local_rows, int64_t* local_cols);
+
+/* Y = XW under SBP (Sec. 3.1, Table 1): every device i multiplies the local
+ * tensors it holds, Y_i = X_i W_i, in ONE grouped launch over the k shards.
+ *   x [M,K], w [K,N], y [M,N] global shapes; x and w share a dtype.
+ *   sbp_y must be the Table-1 result or SBP_AUTO.
+ *   dtype of y: P(sum) results are always SBP_F32 (un-reduced partials keep the
+ *   accumulator's precision); S / B results have the inputs' dtype.  bf16
+ *   inputs accumulate in fp32 and round once, to nearest even.
+ *   A P(sum) input operand (rows 4, 5 of Table 1) must be SBP_F32 and so must
+ *   the other operand.
+ *   k-way results are written to y->shard[i]; x, w are read only. */
+int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w, sbp_t sbp_w,
+                   const sbp_tensor_t* y, sbp_t sbp_y, int32_t k, void* stream);
+
+/* sbp_matmul with an elementwise epilogue fused before the store (SBP_EPI_*). */
+int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w, sbp_t sbp_w,
+                      const sbp_tensor_t* y, sbp_t sbp_y, int32_t k, void* stream,
+                      int32_t epilogue);
+
+/* Boxing (Sec. 3.2, Table 2, same device set): rewrite the k local tensors of one
+ * global tensor from sbp_in to sbp_out; the global tensor is unchanged.
+ *   P(sum)/P(max) -> B      all-reduce:      out_j = op_i in_i            for every j
+ *   P(sum)/P(max) -> S(a)   reduce-scatter:  out_j = op_i in_i[slice_j]
+ *   S(a) -> B               all-gather:      out_j = concat_i in_i        for every j
+ *   S(a) -> S(b), a != b    all2all:         out_j = concat_i in_i[slice_j along b]
+ *   B -> S(a)               local slice:     out_j = in_j[slice_j]  (its OWN copy)
+ *   S(a)->S(a), B->B, P->P  identity copies
+ *   S(a) -> P(sum), B -> P(sum)   zero-cost forms: every device keeps the values it
+ *                           already holds and zero-fills the rest (B: device 0 keeps).
+ * in->rows/cols/dtype must equal out's; P tensors must be SBP_F32; reductions are
+ * done in fp32 in shard order i = 0 .. k-1, so every B copy is bit-identical and
+ * runs are bit-reproducible.  S/B -> S/B moves raw words and never interprets
+ * them (NaN patterns survive).  trans must be 0 on both sides. */
+int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out, sbp_t sbp_out,
+                   int32_t k, void* stream);
+
+/* Local reductions of the model-parallel softmax (Sec. 6.3.1): logits [R, C] are
+ * S(1); each device reduces the columns it holds.
+ *   sbp_row_max:    m_i[r] = max_c L_i[r, c]              -> out [R,1] f32, P(max)
+ *   sbp_row_sumexp: s_i[r] = sum_c exp(L_i[r, c] - m[r])  -> out [R,1] f32, P(sum)
+ * gmax is the B tensor [R,1] f32 obtained by boxing the P(max) to B.  Statistics
+ * are taken over the logits as stored (bf16 or f32), in fp32.  A device that
+ * holds no column writes the identity (-inf, 0).  sbp_l other than S(1) does not
+ * yield partial vectors and is rejected with SBP_ERR_UNSUPPORTED. */
+int32_t sbp_row_max(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_t* out,
+                    int32_t k, void* stream);
+int32_t sbp_row_sumexp(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_t* gmax,
+                       const sbp_tensor_t* out, int32_t k, void* stream);
+
+/* Tuning knobs; they never change what is computed beyond fp32 summation order
+ * inside a GEMM tile.  Unknown knob or value: SBP_ERR_UNSUPPORTED. */
+enum {
+    SBP_KNOB_GEMM_VARIANT = 0   /* 0 = default choice by shape; >0 forces a kernel variant */
+};
+int32_t sbp_set_knob(int32_t knob, int32_t value);
+
+/* Static, NUL-terminated description of a status code. */
+const char* sbp_strerror(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBP_MI355X_H */

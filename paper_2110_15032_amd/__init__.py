@@ -1,0 +1,13 @@
+"""MI355X-native SBP matmul + boxing: thin Python binding over libsbp_mi355x.so.
+
+Everything here is argument marshalling for the C ABI declared in include/sbp.h; all
+computation runs in the HIP library.  PyTorch is used by callers for device memory and
+streams only.  Importing the package does not need a GPU; loading the library does need
+the built .so (python -m paper_2110_15032_amd.build) and fails loudly without it.
+"""
+from .binding import (  # noqa: F401
+    S, B, P_SUM, P_MAX, AUTO, F32, BF16, EPI_NONE, EPI_GELU, KNOB_GEMM_VARIANT,
+    SbpError, SbpTensor, lib, lib_path,
+    sbp_infer_matmul, sbp_local_shape, sbp_matmul, sbp_matmul_ex, sbp_boxing,
+    sbp_row_max, sbp_row_sumexp, sbp_set_knob, sbp_strerror, EXPORTS,
+)

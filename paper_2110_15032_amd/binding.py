@@ -1,0 +1,147 @@
+"""ctypes binding with the same names as the C ABI (include/sbp.h)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libsbp_mi355x.so")
+
+# signatures (sbp_t)
+def S(axis: int) -> int:
+    return int(axis)
+B = -1
+P_SUM = -2
+P_MAX = -3
+AUTO = -100
+# dtypes
+F32 = 0
+BF16 = 1
+# epilogues
+EPI_NONE = 0
+EPI_GELU = 1
+# knobs
+KNOB_GEMM_VARIANT = 0
+
+#: every symbol include/sbp.h declares
+EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing",
+           "sbp_row_max", "sbp_row_sumexp", "sbp_set_knob", "sbp_strerror")
+
+
+class _CTensor(ctypes.Structure):
+    _fields_ = [("shard", ctypes.POINTER(ctypes.c_void_p)),
+                ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("dtype", ctypes.c_int32), ("trans", ctypes.c_int32)]
+
+
+class SbpError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({sbp_strerror(status)})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsbp_mi355x.so.  There is no fallback: without the library nothing runs."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2110_15032_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        T = ctypes.POINTER(_CTensor)
+        L.sbp_infer_matmul.argtypes = [i32, i32, ctypes.POINTER(i32)]
+        L.sbp_local_shape.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.sbp_matmul.argtypes = [T, i32, T, i32, T, i32, i32, vp]
+        L.sbp_matmul_ex.argtypes = [T, i32, T, i32, T, i32, i32, vp, i32]
+        L.sbp_boxing.argtypes = [T, i32, T, i32, i32, vp]
+        L.sbp_row_max.argtypes = [T, i32, T, i32, vp]
+        L.sbp_row_sumexp.argtypes = [T, i32, T, T, i32, vp]
+        L.sbp_set_knob.argtypes = [i32, i32]
+        L.sbp_strerror.argtypes = [i32]
+        L.sbp_strerror.restype = ctypes.c_char_p
+        for f in EXPORTS[:-1]:
+            getattr(L, f).restype = i32
+        _lib = L
+    return _lib
+
+
+class SbpTensor:
+    """A global tensor as the ABI sees it: k device pointers + global shape + dtype + trans.
+
+    `shards` are integers (device addresses) or objects with .data_ptr() (torch tensors); the
+    object keeps them alive.  Nothing is copied."""
+
+    def __init__(self, shards: Sequence, rows: int, cols: int, dtype: int, trans: int = 0):
+        self.keep = list(shards)
+        ptrs = [s if isinstance(s, int) or s is None else s.data_ptr() for s in shards]
+        self.k = len(ptrs)
+        self._arr = (ctypes.c_void_p * max(1, self.k))(*ptrs)
+        self.c = _CTensor(ctypes.cast(self._arr, ctypes.POINTER(ctypes.c_void_p)), rows, cols, dtype, trans)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def _stream_ptr(stream) -> ctypes.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    return ctypes.c_void_p(stream)
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise SbpError(status, what)
+
+
+def sbp_strerror(status: int) -> str:
+    return lib().sbp_strerror(status).decode()
+
+
+def sbp_infer_matmul(sbp_x: int, sbp_w: int) -> int:
+    out = ctypes.c_int32()
+    _check(lib().sbp_infer_matmul(sbp_x, sbp_w, ctypes.byref(out)), "sbp_infer_matmul")
+    return out.value
+
+
+def sbp_local_shape(rows: int, cols: int, sbp: int, k: int, i: int) -> tuple[int, int]:
+    r, c = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().sbp_local_shape(rows, cols, sbp, k, i, ctypes.byref(r), ctypes.byref(c)), "sbp_local_shape")
+    return r.value, c.value
+
+
+def sbp_matmul(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTensor, sbp_y: int, k: int,
+               stream=None) -> None:
+    _check(lib().sbp_matmul(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, k, _stream_ptr(stream)), "sbp_matmul")
+
+
+def sbp_matmul_ex(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTensor, sbp_y: int, k: int,
+                  stream=None, epilogue: int = EPI_NONE) -> None:
+    _check(lib().sbp_matmul_ex(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, k, _stream_ptr(stream), epilogue),
+           "sbp_matmul_ex")
+
+
+def sbp_boxing(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
+    _check(lib().sbp_boxing(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing")
+
+
+def sbp_row_max(logits: SbpTensor, sbp_l: int, out: SbpTensor, k: int, stream=None) -> None:
+    _check(lib().sbp_row_max(logits.ref(), sbp_l, out.ref(), k, _stream_ptr(stream)), "sbp_row_max")
+
+
+def sbp_row_sumexp(logits: SbpTensor, sbp_l: int, gmax: SbpTensor, out: SbpTensor, k: int, stream=None) -> None:
+    _check(lib().sbp_row_sumexp(logits.ref(), sbp_l, gmax.ref(), out.ref(), k, _stream_ptr(stream)), "sbp_row_sumexp")
+
+
+def sbp_set_knob(knob: int, value: int) -> None:
+    _check(lib().sbp_set_knob(knob, value), "sbp_set_knob")

@@ -1,0 +1,314 @@
+// Boxing kernels (paper Sec. 3.2, Table 2, same device set), for k shard buffers in one HBM.
+//
+// Every conversion is a set of rectangle tasks (blockIdx.y = task).  A task reads one rows x cols
+// rectangle from NS source shards that all use the same offset and pitch, combines them in shard
+// order (copy / fp32 sum / fp32 max) and writes the result into ND destination shards that all use
+// the same offset and pitch.  The rectangles follow from the balanced split alone, so the kernel
+// derives them from (mode, task id) and needs no task table in memory:
+//
+//   P -> B        1 task : all k sources, all k destinations, whole tensor       (all-reduce)
+//   P -> S(a)     k tasks: all k sources at slice j        -> out_j              (reduce-scatter)
+//   S(a) -> B     k tasks: in_i                            -> slice i of all k   (all-gather)
+//   S(a) -> S(b)  k*k    : in_i restricted to slice j of b -> out_j at slice i   (all2all)
+//   B -> S(a)     k tasks: slice j of in_j (its own copy)  -> out_j              (local slice)
+//   X -> X        k tasks: in_i -> out_i                                         (identity)
+//
+// HBM-bound: every input byte is read once and every output byte written once, with the widest
+// vector (up to 16 B per lane) that all offsets and pitches of the conversion allow.
+#include "sbp_internal.h"
+
+namespace sbp {
+namespace {
+
+enum BoxMode : int32_t { M_P2B = 0, M_P2S, M_S2B, M_S2S, M_B2S, M_IDENT };
+
+struct BoxParams {
+    const void* src[SBP_MAX_K];
+    void* dst[SBP_MAX_K];
+    int64_t rows, cols;   // global shape in elements
+    int32_t k;
+    int32_t mode;
+    int32_t axis_in;      // split axis of the input  (S inputs), else -1
+    int32_t axis_out;     // split axis of the output (S outputs), else -1
+    int32_t vec_elems;    // elements per vector access
+    int32_t sbp_same;     // M_IDENT: signature (decides the local shape)
+};
+
+struct Task {
+    int32_t s0, ns;       // sources  [s0, s0 + ns)
+    int32_t d0, nd;       // destinations
+    int64_t src_off, dst_off, src_ld, dst_ld;   // elements
+    int64_t rows, cols;   // rectangle, elements
+};
+
+__host__ __device__ inline void range_of(int64_t n, int32_t k, int32_t i, int32_t axis_is_split, int64_t& b, int64_t& l) {
+    if (axis_is_split) {
+        b = split_begin(n, k, i);
+        l = split_len(n, k, i);
+    } else {
+        b = 0;
+        l = n;
+    }
+}
+
+// Geometry of task t.  Shared by the launcher (alignment analysis, grid sizing) and the kernel.
+__host__ __device__ inline Task make_task(const BoxParams& p, int32_t t) {
+    Task T{};
+    const int32_t k = p.k;
+    int64_t rb, rl, cb, cl;
+    switch (p.mode) {
+        case M_P2B:
+            T = {0, k, 0, k, 0, 0, p.cols, p.cols, p.rows, p.cols};
+            break;
+        case M_P2S: {
+            range_of(p.rows, k, t, p.axis_out == 0, rb, rl);
+            range_of(p.cols, k, t, p.axis_out == 1, cb, cl);
+            T = {0, k, t, 1, rb * p.cols + cb, 0, p.cols, cl, rl, cl};
+            break;
+        }
+        case M_S2B: {
+            range_of(p.rows, k, t, p.axis_in == 0, rb, rl);
+            range_of(p.cols, k, t, p.axis_in == 1, cb, cl);
+            T = {t, 1, 0, k, 0, rb * p.cols + cb, cl, p.cols, rl, cl};
+            break;
+        }
+        case M_S2S: {
+            const int32_t i = t / k, j = t % k;   // in_i -> out_j, axis_in != axis_out
+            int64_t irb, irl, icb, icl, orb, orl, ocb, ocl;
+            range_of(p.rows, k, i, p.axis_in == 0, irb, irl);
+            range_of(p.cols, k, i, p.axis_in == 1, icb, icl);
+            range_of(p.rows, k, j, p.axis_out == 0, orb, orl);
+            range_of(p.cols, k, j, p.axis_out == 1, ocb, ocl);
+            // intersection in global coordinates: one side is split by rows, the other by columns
+            const int64_t r0 = irb > orb ? irb : orb, r1 = (irb + irl) < (orb + orl) ? (irb + irl) : (orb + orl);
+            const int64_t c0 = icb > ocb ? icb : ocb, c1 = (icb + icl) < (ocb + ocl) ? (icb + icl) : (ocb + ocl);
+            T = {i, 1, j, 1, (r0 - irb) * icl + (c0 - icb), (r0 - orb) * ocl + (c0 - ocb), icl, ocl, r1 - r0, c1 - c0};
+            break;
+        }
+        case M_B2S: {
+            range_of(p.rows, k, t, p.axis_out == 0, rb, rl);
+            range_of(p.cols, k, t, p.axis_out == 1, cb, cl);
+            T = {t, 1, t, 1, rb * p.cols + cb, 0, p.cols, cl, rl, cl};
+            break;
+        }
+        default: {  // M_IDENT
+            range_of(p.rows, k, t, p.sbp_same == 0, rb, rl);
+            range_of(p.cols, k, t, p.sbp_same == 1, cb, cl);
+            T = {t, 1, t, 1, 0, 0, cl, cl, rl, cl};
+            break;
+        }
+    }
+    // A rectangle as wide as both pitches is one contiguous run: flatten it so the kernel's
+    // row / column split degenerates (no division on the hot path).
+    if (T.cols == T.src_ld && T.cols == T.dst_ld) {
+        T.cols = T.rows * T.cols;
+        T.rows = T.cols ? 1 : 0;
+        T.src_ld = T.dst_ld = T.cols;
+    }
+    return T;
+}
+
+// native clang vectors: one global_load / global_store of 4, 8 or 16 bytes per lane
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <int OP, typename V>
+__device__ inline V combine(V a, V b) {
+    if constexpr (OP == BOX_SUM) return a + b;
+    else return __builtin_elementwise_max(a, b);
+}
+
+constexpr int BOX_THREADS = 256;
+
+// Reduction tasks: NS sources (compile-time when KS > 0), fp32 math in shard order.
+template <typename V, int OP, int KS, int UNROLL>
+__global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
+    const Task T = make_task(p, blockIdx.y);
+    const int32_t ns = KS > 0 ? KS : T.ns;
+    const uint32_t cols_v = (uint32_t)(T.cols / p.vec_elems);
+    const uint32_t total = (uint32_t)T.rows * cols_v;
+    const int64_t src_ld_v = T.src_ld / p.vec_elems, dst_ld_v = T.dst_ld / p.vec_elems;
+    const int64_t src_off_v = T.src_off / p.vec_elems, dst_off_v = T.dst_off / p.vec_elems;
+    const uint32_t stride = gridDim.x * BOX_THREADS;
+    for (uint32_t base = blockIdx.x * BOX_THREADS + threadIdx.x; base < total; base += stride * UNROLL) {
+        V acc[UNROLL];
+        int64_t dpos[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t idx = base + u * stride;
+            if (idx < total) {
+                const uint32_t r = T.rows == 1 ? 0 : idx / cols_v;
+                const uint32_t c = idx - r * cols_v;
+                const int64_t spos = src_off_v + (int64_t)r * src_ld_v + c;
+                dpos[u] = dst_off_v + (int64_t)r * dst_ld_v + c;
+                V a = __builtin_nontemporal_load(static_cast<const V*>(p.src[0]) + spos);
+                if constexpr (KS > 0) {
+                    V part[KS];
+#pragma unroll
+                    for (int i = 1; i < KS; ++i) part[i] = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos);
+#pragma unroll
+                    for (int i = 1; i < KS; ++i) a = combine<OP>(a, part[i]);
+                } else {
+                    for (int i = 1; i < ns; ++i) {
+                        const V b = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos);
+                        a = combine<OP>(a, b);
+                    }
+                }
+                acc[u] = a;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t idx = base + u * stride;
+            if (idx < total) {
+                for (int j = 0; j < T.nd; ++j) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[T.d0 + j]) + dpos[u]);
+            }
+        }
+    }
+}
+
+// Copy tasks: one source, ND destinations, raw words.
+template <typename V, int UNROLL>
+__global__ __launch_bounds__(BOX_THREADS) void box_copy_kernel(BoxParams p) {
+    const Task T = make_task(p, blockIdx.y);
+    const uint32_t cols_v = (uint32_t)(T.cols / p.vec_elems);
+    const uint32_t total = (uint32_t)T.rows * cols_v;
+    const int64_t src_ld_v = T.src_ld / p.vec_elems, dst_ld_v = T.dst_ld / p.vec_elems;
+    const V* __restrict__ src = static_cast<const V*>(p.src[T.s0]) + T.src_off / p.vec_elems;
+    const int64_t dst_off_v = T.dst_off / p.vec_elems;
+    const uint32_t stride = gridDim.x * BOX_THREADS;
+    for (uint32_t base = blockIdx.x * BOX_THREADS + threadIdx.x; base < total; base += stride * UNROLL) {
+        V val[UNROLL];
+        int64_t dpos[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t idx = base + u * stride;
+            if (idx < total) {
+                const uint32_t r = T.rows == 1 ? 0 : idx / cols_v;
+                const uint32_t c = idx - r * cols_v;
+                val[u] = __builtin_nontemporal_load(src + (int64_t)r * src_ld_v + c);
+                dpos[u] = dst_off_v + (int64_t)r * dst_ld_v + c;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t idx = base + u * stride;
+            if (idx < total) {
+                for (int j = 0; j < T.nd; ++j) __builtin_nontemporal_store(val[u], static_cast<V*>(p.dst[T.d0 + j]) + dpos[u]);
+            }
+        }
+    }
+}
+
+inline int64_t gcd64(int64_t a, int64_t b) {
+    while (b) {
+        const int64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    return a < 0 ? -a : a;
+}
+
+template <typename V, int OP, int UNROLL>
+void launch_reduce_k(const BoxParams& p, dim3 grid, hipStream_t st) {
+    switch (p.k) {
+        case 2: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 2, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
+        case 4: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 4, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
+        case 8: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 8, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
+        case 16: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 16, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
+        default: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 0, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
+    }
+}
+
+template <int OP>
+void launch_reduce(const BoxParams& p, dim3 grid, hipStream_t st) {
+    if (p.vec_elems == 4) launch_reduce_k<f32x4, OP, 2>(p, grid, st);
+    else if (p.vec_elems == 2) launch_reduce_k<f32x2, OP, 2>(p, grid, st);
+    else launch_reduce_k<float, OP, 2>(p, grid, st);
+}
+
+}  // namespace
+
+int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
+    BoxParams p{};
+    p.rows = plan.rows;
+    p.cols = plan.cols;
+    p.k = plan.k;
+    p.axis_in = (plan.sbp_in == SBP_S(0) || plan.sbp_in == SBP_S(1)) ? plan.sbp_in : -1;
+    p.axis_out = (plan.sbp_out == SBP_S(0) || plan.sbp_out == SBP_S(1)) ? plan.sbp_out : -1;
+    for (int i = 0; i < plan.k; ++i) {
+        p.src[i] = plan.src[i];
+        p.dst[i] = plan.dst[i];
+    }
+    const bool p_in = plan.sbp_in == SBP_P_SUM || plan.sbp_in == SBP_P_MAX;
+    const bool p_out = plan.sbp_out == SBP_P_SUM || plan.sbp_out == SBP_P_MAX;
+    int32_t tasks;
+    if (plan.sbp_in == plan.sbp_out) {
+        p.mode = M_IDENT;
+        p.sbp_same = plan.sbp_in;
+        tasks = plan.k;
+    } else if (p_out) {
+        return SBP_ERR_UNSUPPORTED;  // S -> P, B -> P: zero-cost forms, not built yet
+    } else if (p_in && plan.sbp_out == SBP_B) {
+        p.mode = M_P2B;
+        tasks = 1;
+    } else if (p_in) {
+        p.mode = M_P2S;
+        tasks = plan.k;
+    } else if (plan.sbp_in == SBP_B) {
+        p.mode = M_B2S;
+        tasks = plan.k;
+    } else if (plan.sbp_out == SBP_B) {
+        p.mode = M_S2B;
+        tasks = plan.k;
+    } else {
+        p.mode = M_S2S;
+        tasks = plan.k * plan.k;
+    }
+    if (tasks > 65535) return SBP_ERR_UNSUPPORTED;
+
+    // widest vector every task allows: all offsets, pitches and widths must be multiples of it
+    int64_t g = 16 / plan.elem_bytes;  // elements in 16 bytes
+    p.vec_elems = 1;                   // make_task does not depend on it
+    int64_t max_units = 0;
+    for (int32_t t = 0; t < tasks; ++t) {
+        const Task T = make_task(p, t);
+        if (T.rows * T.cols == 0) continue;
+        g = gcd64(g, T.cols);
+        g = gcd64(g, T.src_off);
+        g = gcd64(g, T.dst_off);
+        if (T.rows > 1) {
+            g = gcd64(g, T.src_ld);
+            g = gcd64(g, T.dst_ld);
+        }
+        max_units = T.rows * T.cols > max_units ? T.rows * T.cols : max_units;
+    }
+    if (max_units == 0) return SBP_OK;  // nothing to move
+    p.vec_elems = (int32_t)g;
+    max_units /= g;
+    if (max_units >= (int64_t)1 << 31) return SBP_ERR_UNSUPPORTED;
+
+    const bool reduce = p_in && plan.sbp_in != plan.sbp_out;
+    const int unroll = reduce ? 2 : 4;
+    int64_t bx = (max_units + (int64_t)BOX_THREADS * unroll - 1) / ((int64_t)BOX_THREADS * unroll);
+    const int64_t cap = (8192 + tasks - 1) / tasks;  // about 32 blocks per CU over the whole launch
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    const dim3 grid((uint32_t)bx, (uint32_t)tasks);
+
+    if (reduce) {
+        if (plan.sbp_in == SBP_P_SUM) launch_reduce<BOX_SUM>(p, grid, stream);
+        else launch_reduce<BOX_MAX>(p, grid, stream);
+    } else {
+        const int vb = p.vec_elems * plan.elem_bytes;
+        if (vb == 16) hipLaunchKernelGGL((box_copy_kernel<u32x4, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
+        else if (vb == 8) hipLaunchKernelGGL((box_copy_kernel<u32x2, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
+        else if (vb == 4) hipLaunchKernelGGL((box_copy_kernel<uint32_t, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
+        else hipLaunchKernelGGL((box_copy_kernel<uint16_t, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
+    }
+    return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+}
+
+}  // namespace sbp

@@ -1,0 +1,260 @@
+// Host side of the C ABI: argument validation, Table-1 deduction, shard geometry and dispatch.
+// Every check runs before anything is enqueued, so a failed call has no effect on the stream.
+#include <algorithm>
+#include <atomic>
+#include <vector>
+
+#include "sbp_internal.h"
+
+namespace {
+
+using namespace sbp;
+
+std::atomic<int32_t> g_gemm_variant{0};
+
+bool is_sbp(sbp_t s) { return s == SBP_S(0) || s == SBP_S(1) || s == SBP_B || s == SBP_P_SUM || s == SBP_P_MAX; }
+bool is_partial(sbp_t s) { return s == SBP_P_SUM || s == SBP_P_MAX; }
+int elem_bytes(int32_t dtype) { return dtype == SBP_BF16 ? 2 : 4; }
+
+struct Local {
+    int64_t rows, cols;
+};
+Local local_of(int64_t rows, int64_t cols, sbp_t s, int32_t k, int32_t i) {
+    if (s == SBP_S(0)) return {split_len(rows, k, i), cols};
+    if (s == SBP_S(1)) return {rows, split_len(cols, k, i)};
+    return {rows, cols};
+}
+
+int32_t check_tensor(const sbp_tensor_t* t, sbp_t s, int32_t k) {
+    if (!t || !t->shard) return SBP_ERR_NULL;
+    if (t->rows < 0 || t->cols < 0) return SBP_ERR_SHAPE;
+    if (t->dtype != SBP_F32 && t->dtype != SBP_BF16) return SBP_ERR_DTYPE;
+    if (t->trans != 0 && t->trans != 1) return SBP_ERR_SHAPE;
+    if (!is_sbp(s)) return SBP_ERR_AXIS;
+    for (int32_t i = 0; i < k; ++i) {
+        const Local l = local_of(t->rows, t->cols, s, k, i);
+        if (l.rows * l.cols == 0) continue;  // an empty local tensor needs no storage
+        if (!t->shard[i]) return SBP_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(t->shard[i]) & 15u) return SBP_ERR_ALIGN;
+    }
+    return SBP_OK;
+}
+
+struct Span {
+    uintptr_t lo, hi;
+};
+void spans_of(const sbp_tensor_t* t, sbp_t s, int32_t k, std::vector<Span>& v) {
+    for (int32_t i = 0; i < k; ++i) {
+        const Local l = local_of(t->rows, t->cols, s, k, i);
+        const uintptr_t bytes = (uintptr_t)(l.rows * l.cols) * elem_bytes(t->dtype);
+        if (bytes == 0) continue;
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(t->shard[i]);
+        v.push_back({lo, lo + bytes});
+    }
+}
+bool overlap(const Span& a, const Span& b) { return a.lo < b.hi && b.lo < a.hi; }
+
+// outputs must be pairwise disjoint and disjoint from every input
+int32_t check_alias(const std::vector<Span>& outs, const std::vector<Span>& ins) {
+    for (size_t a = 0; a < outs.size(); ++a) {
+        for (size_t b = a + 1; b < outs.size(); ++b)
+            if (overlap(outs[a], outs[b])) return SBP_ERR_ALIAS;
+        for (const Span& in : ins)
+            if (overlap(outs[a], in)) return SBP_ERR_ALIAS;
+    }
+    return SBP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sbp_strerror(int32_t status) {
+    switch (status) {
+        case SBP_OK: return "ok";
+        case SBP_ERR_NULL: return "null descriptor, shard array or shard pointer";
+        case SBP_ERR_K: return "k out of range";
+        case SBP_ERR_SHAPE: return "bad or incompatible shape";
+        case SBP_ERR_DTYPE: return "dtype not allowed here";
+        case SBP_ERR_AXIS: return "not an SBP signature";
+        case SBP_ERR_SIGNATURE: return "signature pair not valid for MatMul, or output signature is not the deduced one";
+        case SBP_ERR_ALIAS: return "output buffer overlaps another buffer";
+        case SBP_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case SBP_ERR_UNSUPPORTED: return "valid request without a kernel in this build";
+        case SBP_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int32_t sbp_set_knob(int32_t knob, int32_t value) {
+    if (knob == SBP_KNOB_GEMM_VARIANT && value >= 0 && value < 64) {
+        g_gemm_variant.store(value);
+        return SBP_OK;
+    }
+    return SBP_ERR_UNSUPPORTED;
+}
+
+int32_t sbp_infer_matmul(sbp_t sx, sbp_t sw, sbp_t* sy) {
+    if (!sy) return SBP_ERR_NULL;
+    if (!is_sbp(sx) || !is_sbp(sw)) return SBP_ERR_AXIS;
+    // Table 1: the six valid rows, in the paper's order.
+    if (sx == SBP_S(0) && sw == SBP_B) { *sy = SBP_S(0); return SBP_OK; }
+    if (sx == SBP_B && sw == SBP_S(1)) { *sy = SBP_S(1); return SBP_OK; }
+    if (sx == SBP_S(1) && sw == SBP_S(0)) { *sy = SBP_P_SUM; return SBP_OK; }
+    if (sx == SBP_P_SUM && sw == SBP_B) { *sy = SBP_P_SUM; return SBP_OK; }
+    if (sx == SBP_B && sw == SBP_P_SUM) { *sy = SBP_P_SUM; return SBP_OK; }
+    if (sx == SBP_B && sw == SBP_B) { *sy = SBP_B; return SBP_OK; }
+    return SBP_ERR_SIGNATURE;
+}
+
+int32_t sbp_local_shape(int64_t rows, int64_t cols, sbp_t s, int32_t k, int32_t i, int64_t* lr, int64_t* lc) {
+    if (!lr || !lc) return SBP_ERR_NULL;
+    if (k < 1 || k > SBP_MAX_K || i < 0 || i >= k) return SBP_ERR_K;
+    if (rows < 0 || cols < 0) return SBP_ERR_SHAPE;
+    if (!is_sbp(s)) return SBP_ERR_AXIS;
+    const Local l = local_of(rows, cols, s, k, i);
+    *lr = l.rows;
+    *lc = l.cols;
+    return SBP_OK;
+}
+
+int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,
+                      sbp_t sy, int32_t k, void* stream, int32_t epilogue) {
+    if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
+    if (!x || !w || !y) return SBP_ERR_NULL;
+    if (!is_sbp(sx) || !is_sbp(sw)) return SBP_ERR_AXIS;
+    sbp_t deduced;
+    int32_t st = sbp_infer_matmul(sx, sw, &deduced);
+    if (st != SBP_OK) return st;
+    if (sy == SBP_AUTO) sy = deduced;
+    if (!is_sbp(sy)) return SBP_ERR_AXIS;
+    if (sy != deduced) return SBP_ERR_SIGNATURE;
+    if ((st = check_tensor(x, sx, k)) != SBP_OK) return st;
+    if ((st = check_tensor(w, sw, k)) != SBP_OK) return st;
+    if ((st = check_tensor(y, sy, k)) != SBP_OK) return st;
+    if (x->cols != w->rows || y->rows != x->rows || y->cols != w->cols) return SBP_ERR_SHAPE;
+    if (x->dtype != w->dtype) return SBP_ERR_DTYPE;
+    if ((is_partial(sx) || is_partial(sw)) && x->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    const int32_t want_out = is_partial(sy) ? SBP_F32 : x->dtype;
+    if (y->dtype != want_out) return SBP_ERR_DTYPE;
+    if (y->trans != 0) return SBP_ERR_UNSUPPORTED;
+    if (epilogue != SBP_EPI_NONE && epilogue != SBP_EPI_GELU) return SBP_ERR_UNSUPPORTED;
+    if (epilogue == SBP_EPI_GELU && is_partial(sy)) return SBP_ERR_SIGNATURE;
+    if (x->rows > INT32_MAX || x->cols > INT32_MAX || w->cols > INT32_MAX) return SBP_ERR_UNSUPPORTED;
+
+    std::vector<Span> ins, outs;
+    spans_of(x, sx, k, ins);
+    spans_of(w, sw, k, ins);
+    spans_of(y, sy, k, outs);
+    // a B output written k times to one buffer would be k writers of the same bytes: refuse it too
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    GemmPlan plan{};
+    plan.groups = k;
+    plan.in_dtype = x->dtype;
+    plan.out_dtype = y->dtype;
+    plan.a_kc = x->trans ? 0 : 1;
+    plan.b_kc = w->trans ? 1 : 0;
+    plan.epilogue = epilogue;
+    for (int32_t i = 0; i < k; ++i) {
+        const Local lx = local_of(x->rows, x->cols, sx, k, i);
+        const Local lw = local_of(w->rows, w->cols, sw, k, i);
+        const Local ly = local_of(y->rows, y->cols, sy, k, i);
+        if (lx.cols != lw.rows || ly.rows != lx.rows || ly.cols != lw.cols) return SBP_ERR_SHAPE;
+        GemmShard& g = plan.s[i];
+        g.a = x->shard[i];
+        g.b = w->shard[i];
+        g.c = y->shard[i];
+        g.m = (int32_t)lx.rows;
+        g.n = (int32_t)lw.cols;
+        g.kk = (int32_t)lx.cols;
+        g.lda = (int32_t)(x->trans ? lx.rows : lx.cols);
+        g.ldb = (int32_t)(w->trans ? lw.rows : lw.cols);
+        g.ldc = (int32_t)ly.cols;
+    }
+    return launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,
+                   sbp_t sy, int32_t k, void* stream) {
+    return sbp_matmul_ex(x, sx, w, sw, y, sy, k, stream, SBP_EPI_NONE);
+}
+
+int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
+                   void* stream) {
+    if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
+    if (!in || !out) return SBP_ERR_NULL;
+    int32_t st;
+    if ((st = check_tensor(in, s_in, k)) != SBP_OK) return st;
+    if ((st = check_tensor(out, s_out, k)) != SBP_OK) return st;
+    if (in->rows != out->rows || in->cols != out->cols) return SBP_ERR_SHAPE;
+    if (in->dtype != out->dtype) return SBP_ERR_DTYPE;
+    if ((is_partial(s_in) || is_partial(s_out)) && in->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    if (in->trans || out->trans) return SBP_ERR_UNSUPPORTED;
+    if (is_partial(s_in) && is_partial(s_out) && s_in != s_out) return SBP_ERR_SIGNATURE;
+    if (s_out == SBP_P_MAX && !is_partial(s_in)) return SBP_ERR_UNSUPPORTED;
+
+    std::vector<Span> ins, outs;
+    spans_of(in, s_in, k, ins);
+    spans_of(out, s_out, k, outs);
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    BoxPlan plan{};
+    plan.rows = in->rows;
+    plan.cols = in->cols;
+    plan.k = k;
+    plan.sbp_in = s_in;
+    plan.sbp_out = s_out;
+    plan.elem_bytes = elem_bytes(in->dtype);
+    for (int32_t i = 0; i < k; ++i) {
+        plan.src[i] = in->shard[i];
+        plan.dst[i] = out->shard[i];
+    }
+    return launch_boxing(plan, static_cast<hipStream_t>(stream));
+}
+
+static int32_t row_stat(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* gmax, const sbp_tensor_t* out,
+                        int32_t k, void* stream, bool sumexp) {
+    if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
+    if (!logits || !out || (sumexp && !gmax)) return SBP_ERR_NULL;
+    int32_t st;
+    if ((st = check_tensor(logits, sl, k)) != SBP_OK) return st;
+    if (is_partial(sl)) return SBP_ERR_SIGNATURE;  // row statistics of an un-reduced partial are meaningless
+    if (sl != SBP_S(1)) return SBP_ERR_UNSUPPORTED;  // only the model-parallel case yields partial vectors
+    const sbp_t s_out = sumexp ? SBP_P_SUM : SBP_P_MAX;
+    if ((st = check_tensor(out, s_out, k)) != SBP_OK) return st;
+    if (sumexp && (st = check_tensor(gmax, SBP_B, k)) != SBP_OK) return st;
+    if (out->rows != logits->rows || out->cols != 1 || out->dtype != SBP_F32) return SBP_ERR_SHAPE;
+    if (sumexp && (gmax->rows != logits->rows || gmax->cols != 1 || gmax->dtype != SBP_F32)) return SBP_ERR_SHAPE;
+    if (logits->trans || out->trans || (sumexp && gmax->trans)) return SBP_ERR_UNSUPPORTED;
+    if (logits->cols > INT32_MAX) return SBP_ERR_UNSUPPORTED;
+
+    std::vector<Span> ins, outs;
+    spans_of(logits, sl, k, ins);
+    if (sumexp) spans_of(gmax, SBP_B, k, ins);
+    spans_of(out, s_out, k, outs);
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    RowStatPlan plan{};
+    plan.rows = logits->rows;
+    plan.k = k;
+    plan.dtype = logits->dtype;
+    for (int32_t i = 0; i < k; ++i) {
+        plan.logits[i] = logits->shard[i];
+        plan.gmax[i] = sumexp ? static_cast<const float*>(gmax->shard[i]) : nullptr;
+        plan.out[i] = static_cast<float*>(out->shard[i]);
+        plan.cols[i] = (int32_t)local_of(logits->rows, logits->cols, sl, k, i).cols;
+    }
+    return launch_row_stat(plan, sumexp, static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_row_max(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* out, int32_t k, void* stream) {
+    return row_stat(logits, sl, nullptr, out, k, stream, false);
+}
+
+int32_t sbp_row_sumexp(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* gmax, const sbp_tensor_t* out,
+                       int32_t k, void* stream) {
+    return row_stat(logits, sl, gmax, out, k, stream, true);
+}
+
+}  // extern "C"

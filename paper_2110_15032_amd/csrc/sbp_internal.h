@@ -1,0 +1,77 @@
+// Internal declarations shared by the translation units of libsbp_mi355x.so.
+// Nothing here is part of the C ABI (that is include/sbp.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sbp.h"
+
+namespace sbp {
+
+// Balanced split (paper Sec. 3.1, "in a balanced manner"): floor(n/k) indices per shard,
+// the first n mod k shards one more.  begin(k) == n.
+__host__ __device__ inline int64_t split_begin(int64_t n, int32_t k, int32_t i) {
+    const int64_t q = n / k, r = n % k;
+    return (int64_t)i * q + (i < r ? i : r);
+}
+__host__ __device__ inline int64_t split_len(int64_t n, int32_t k, int32_t i) {
+    return n / k + (i < n % k ? 1 : 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Boxing: every conversion is a set of rectangle tasks.  Task t reads a rows x cols rectangle
+// from n_src source shards (all at the same offset / leading dimension), combines them
+// (copy when n_src == 1, sum or max in shard order otherwise) and writes the result to n_dst
+// destination shards (all at the same offset / leading dimension).
+// ---------------------------------------------------------------------------------------------
+enum BoxOp : int32_t { BOX_COPY = 0, BOX_SUM = 1, BOX_MAX = 2 };
+
+struct BoxPlan {
+    const void* src[SBP_MAX_K];
+    void* dst[SBP_MAX_K];
+    int64_t rows, cols;       // global shape, in elements
+    int32_t k;
+    int32_t sbp_in, sbp_out;  // sbp_t values
+    int32_t elem_bytes;       // 2 or 4
+};
+
+int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
+// Grouped GEMM: shard g computes C_g[m, n] = sum_kk A_g[m, kk] * B_g[kk, n].
+// a_kc: A is stored [m][kk] (kk contiguous, lda = row pitch) else [kk][m].
+// b_kc: B is stored [n][kk] (kk contiguous) else [kk][n].      C is always [m][n], pitch ldc.
+// ---------------------------------------------------------------------------------------------
+struct GemmShard {
+    const void* a;
+    const void* b;
+    void* c;
+    int32_t m, n, kk;
+    int32_t lda, ldb, ldc;
+};
+struct GemmPlan {
+    GemmShard s[SBP_MAX_K];
+    int32_t groups;
+    int32_t in_dtype;   // SBP_F32 | SBP_BF16
+    int32_t out_dtype;  // SBP_F32 | SBP_BF16
+    int32_t a_kc, b_kc;
+    int32_t epilogue;   // SBP_EPI_*
+};
+
+int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
+// Row statistics of the model-parallel softmax.
+// ---------------------------------------------------------------------------------------------
+struct RowStatPlan {
+    const void* logits[SBP_MAX_K];
+    const float* gmax[SBP_MAX_K];   // null for the max pass
+    float* out[SBP_MAX_K];
+    int32_t cols[SBP_MAX_K];        // local column count of every shard (= row pitch)
+    int64_t rows;
+    int32_t k;
+    int32_t dtype;
+};
+int32_t launch_row_stat(const RowStatPlan& plan, bool sumexp, hipStream_t stream);
+
+}  // namespace sbp

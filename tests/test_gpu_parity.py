@@ -1,0 +1,330 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element, on
+seeded inputs small enough for the oracle to finish in seconds but spanning several tiles and
+ragged tails.  Bars: bit-exact for S/B relayout boxing and P(max); 1e-5 * sum|in_i| for fp32
+P(sum) reductions; 2e-2 relative for bf16 matmuls (fp32 accumulate); 1e-5 for fp32 matmuls."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as orc
+import paper_2110_15032_amd as sbp
+import workloads as wl
+from sbp_harness import (DevTensor, TO_ABI, assert_bits_equal, assert_matmul_close, assert_psum_close,
+                         sync, values)
+
+pytestmark = pytest.mark.gpu
+SEED = wl.SEED_BASE
+
+
+def rnd_f32(tid, shape):
+    return wl.normal(SEED, tid, shape).astype(np.float32)
+
+
+def rnd_bf16(tid, shape, std=1.0):
+    return wl.to_bf16_bits(wl.normal(SEED, tid, shape, std))
+
+
+def rnd_words(tid, shape):
+    """arbitrary 16-bit words, NaN / Inf patterns included"""
+    w = wl.uniform(SEED, tid, shape, 0.0, 65536.0).astype(np.uint32).astype(np.uint16)
+    w.flat[:4] = [0x7F80, 0x7FC1, 0xFF80, 0xFFFF][: min(4, w.size)]
+    return w
+
+
+def random_partials(tid, T, k, op):
+    if op == "sum":
+        parts = [rnd_f32(tid + 1 + i, T.shape) for i in range(k - 1)]
+        return parts + [(T - np.sum(parts, axis=0, dtype=np.float32)).astype(np.float32)]
+    return [(T - np.abs(rnd_f32(tid + 1 + i, T.shape)) * (i % 2)).astype(np.float32) for i in range(k)]
+
+
+# ------------------------------------------------------------------------------- boxing
+RELAYOUT = [(a, b) for a, b in itertools.product((orc.S0, orc.S1, orc.B), repeat=2)]
+SHAPES = [(64, 96), (37, 53), (16, 1024), (130, 24), (5, 3)]
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("si,so", RELAYOUT)
+@pytest.mark.parametrize("words", ["u16", "f32"])
+def test_relayout_boxing_is_bit_exact(k, si, so, words):
+    for n, shape in enumerate(SHAPES):
+        T = rnd_words(n, shape) if words == "u16" else rnd_f32(n, shape)
+        ins = orc.scatter(T, si, k)
+        if si == orc.B and so != orc.B:
+            # make the k "copies" differ so that reading the wrong device's copy shows (B -> S)
+            ins = [np.ascontiguousarray(T + (np.uint16(j) if words == "u16" else np.float32(j))) for j in range(k)]
+        ref = orc.boxing(ins, si, so, k)
+        d_in = DevTensor.from_host(ins, *shape, si)
+        d_out = DevTensor.empty(*shape, T.dtype, so, k)
+        sbp.sbp_boxing(d_in.desc, TO_ABI[si], d_out.desc, TO_ABI[so], k)
+        sync()
+        for j, (g, r) in enumerate(zip(d_out.host(), ref)):
+            assert_bits_equal(g, r, f"{si}->{so} k={k} shape={shape} shard {j}")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16, 5])
+@pytest.mark.parametrize("op", ["sum", "max"])
+@pytest.mark.parametrize("so", [orc.B, orc.S0, orc.S1])
+def test_partial_value_boxing(k, op, so):
+    si = orc.P_SUM if op == "sum" else orc.P_MAX
+    for n, shape in enumerate(SHAPES + [(256, 1030)]):
+        T = rnd_f32(100 + n, shape)
+        parts = random_partials(200 + 20 * n, T, k, op)
+        ref = orc.boxing(parts, si, so, k)              # float64
+        d_in = DevTensor.from_host(parts, *shape, si)
+        d_out = DevTensor.empty(*shape, np.float32, so, k)
+        sbp.sbp_boxing(d_in.desc, TO_ABI[si], d_out.desc, TO_ABI[so], k)
+        sync()
+        got = d_out.host()
+        for j in range(k):
+            what = f"P({op})->{so} k={k} shape={shape} shard {j}"
+            assert got[j].shape == ref[j].shape, what
+            if op == "max":
+                assert_bits_equal(got[j], ref[j].astype(np.float32), what)      # max is exact
+            else:
+                local_parts = [orc.boxing([p] * k, orc.B, so, k)[j] for p in parts] if so != orc.B else parts
+                assert_psum_close(got[j], local_parts, ref[j], what)
+        if so == orc.B:
+            for j in range(1, k):
+                assert_bits_equal(got[j], got[0], f"B copies 0 and {j} of P({op})->B")
+
+
+def test_boxing_is_reproducible_run_to_run():
+    k, shape = 8, (512, 640)
+    parts = [rnd_f32(300 + i, shape) for i in range(k)]
+    d_in = DevTensor.from_host(parts, *shape, orc.P_SUM)
+    outs = []
+    for _ in range(2):
+        d_out = DevTensor.empty(*shape, np.float32, orc.B, k)
+        sbp.sbp_boxing(d_in.desc, sbp.P_SUM, d_out.desc, sbp.B, k)
+        sync()
+        outs.append(d_out.host()[0])
+    assert_bits_equal(outs[0], outs[1], "two runs of P(sum)->B")
+    # fp32 sum in shard order is what the library documents: reproduce it exactly
+    acc = parts[0].copy()
+    for p in parts[1:]:
+        acc = (acc + p).astype(np.float32)
+    assert_bits_equal(outs[0], acc, "fp32 shard-order sum")
+
+
+# ------------------------------------------------------------------------------- matmul
+TABLE1 = [(orc.S0, orc.B), (orc.B, orc.S1), (orc.S1, orc.S0), (orc.P_SUM, orc.B), (orc.B, orc.P_SUM), (orc.B, orc.B)]
+
+
+def shard_operand(tid, T, sig, k):
+    if sig == orc.P_SUM:
+        return random_partials(tid, T, k, "sum")
+    return orc.scatter(T, sig, k)
+
+
+def run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx=0, tw=0, epilogue=sbp.EPI_NONE, variant=0):
+    sy = orc.infer_matmul(sx, sw)
+    out_dtype = np.float32 if (sy == orc.P_SUM or Xs[0].dtype == np.float32) else np.uint16
+    dx = DevTensor.from_host(Xs, M, K, sx, trans=tx)
+    dw = DevTensor.from_host(Ws, K, N, sw, trans=tw)
+    dy = DevTensor.empty(M, N, out_dtype, sy, k)
+    sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, variant)
+    try:
+        sbp.sbp_matmul_ex(dx.desc, TO_ABI[sx], dw.desc, TO_ABI[sw], dy.desc, sbp.AUTO, k, None, epilogue)
+        sync()
+    finally:
+        sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, 0)
+    return dy.host(), sy
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+@pytest.mark.parametrize("sx,sw", TABLE1)
+def test_matmul_fp32_every_table1_row(k, sx, sw):
+    M, K, N = 37, 50, 29                       # uneven splits on every axis
+    X, W = rnd_f32(1, (M, K)), rnd_f32(2, (K, N))
+    Xs, Ws = shard_operand(10, X, sx, k), shard_operand(40, W, sw, k)
+    ref, sy = orc.matmul_sbp(Xs, sx, Ws, sw)
+    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k)
+    for i in range(k):
+        assert got[i].shape == ref[i].shape
+        assert_matmul_close(got[i], ref[i], 1e-5, f"fp32 ({sx},{sw}) k={k} shard {i}")
+
+
+@pytest.mark.parametrize("tx,tw", [(0, 0), (1, 0), (0, 1), (1, 1)])
+@pytest.mark.parametrize("sx,sw", [(orc.S0, orc.B), (orc.B, orc.S1), (orc.S1, orc.S0), (orc.B, orc.B)])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_matmul_bf16_mfma_shapes(sx, sw, tx, tw, variant):
+    """several 256-tiles plus ragged M / N tails; K a multiple of 64 per shard.  variant 1 is the
+    generic kernel on the same data (both must agree with the oracle)."""
+    k = 2
+    M, K, N = 2 * 296, 2 * 192, 2 * 328        # per-shard 296 / 192 / 328 when split
+    X, W = rnd_bf16(1, (M, K)), rnd_bf16(2, (K, N), 0.05)
+    Xs, Ws = orc.scatter(X, sx, k), orc.scatter(W, sw, k)
+    ref, sy = orc.matmul_sbp([values(x) for x in Xs], sx, [values(w) for w in Ws], sw)
+    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx, tw, variant=variant)
+    for i in range(k):
+        g = got[i] if sy == orc.P_SUM else values(got[i])
+        assert_matmul_close(g, ref[i], 2e-2, f"bf16 ({sx},{sw}) trans=({tx},{tw}) v{variant} shard {i}")
+        if sy == orc.P_SUM:
+            # fp32 partials of exact bf16 products: only summation order differs from the oracle
+            assert_matmul_close(g, ref[i], 1e-4, f"bf16->f32 partial, shard {i}")
+
+
+def test_matmul_bf16_odd_shapes_fall_back():
+    """pitches that are not multiples of 8 elements, K not a multiple of 64, uneven splits"""
+    k = 3
+    M, K, N = 45, 100, 51
+    X, W = rnd_bf16(1, (M, K)), rnd_bf16(2, (K, N), 0.1)
+    for sx, sw in [(orc.S0, orc.B), (orc.B, orc.S1), (orc.S1, orc.S0)]:
+        Xs, Ws = orc.scatter(X, sx, k), orc.scatter(W, sw, k)
+        ref, sy = orc.matmul_sbp([values(x) for x in Xs], sx, [values(w) for w in Ws], sw)
+        got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k)
+        for i in range(k):
+            g = got[i] if sy == orc.P_SUM else values(got[i])
+            assert_matmul_close(g, ref[i], 2e-2, f"odd ({sx},{sw}) shard {i}")
+
+
+def test_matmul_gelu_epilogue_and_single_rounding():
+    k = 4
+    M, K, N = 256, 128, 4 * 264
+    X, W = rnd_bf16(1, (M, K)), rnd_bf16(2, (K, N), 0.1)
+    Xs, Ws = orc.scatter(X, orc.B, k), orc.scatter(W, orc.S1, k)
+    pre, sy = orc.matmul_sbp([values(x) for x in Xs], orc.B, [values(w) for w in Ws], orc.S1)
+    got, _ = run_matmul(Xs, orc.B, Ws, orc.S1, M, K, N, k, epilogue=sbp.EPI_GELU)
+    for i in range(k):
+        ref = orc.bf16_to_f64(orc.bf16_round(orc.gelu(pre[i])))
+        assert_matmul_close(values(got[i]), ref, 2e-2, f"gelu shard {i}")
+        # far tighter in fact: the bf16 result may differ from the oracle's by one rounding step
+        ulp = np.abs(values(got[i]) - ref) / np.maximum(np.abs(ref), 1e-30)
+        assert np.quantile(ulp, 0.999) <= 2.0 ** -7
+
+
+def test_empty_and_degenerate_shards():
+    # k larger than the split axis: trailing shards are empty
+    k = 8
+    M, K, N = 5, 64, 16
+    X, W = rnd_f32(1, (M, K)), rnd_f32(2, (K, N))
+    Xs, Ws = orc.scatter(X, orc.S0, k), orc.scatter(W, orc.B, k)
+    ref, _ = orc.matmul_sbp(Xs, orc.S0, Ws, orc.B)
+    got, _ = run_matmul(Xs, orc.S0, Ws, orc.B, M, K, N, k)
+    for i in range(k):
+        assert got[i].shape == ref[i].shape
+        if ref[i].size:
+            assert_matmul_close(got[i], ref[i], 1e-5, f"shard {i}")
+    # boxing with empty shards
+    T = rnd_words(5, (3, 40))
+    for si, so in [(orc.S0, orc.S1), (orc.S0, orc.B), (orc.B, orc.S0)]:
+        ins = orc.scatter(T, si, k)
+        d_in = DevTensor.from_host(ins, 3, 40, si)
+        d_out = DevTensor.empty(3, 40, np.uint16, so, k)
+        sbp.sbp_boxing(d_in.desc, TO_ABI[si], d_out.desc, TO_ABI[so], k)
+        sync()
+        for g, r in zip(d_out.host(), orc.boxing(ins, si, so, k)):
+            assert_bits_equal(g, r, f"{si}->{so} with empty shards")
+    # zero-sized global tensor: a no-op that must not fail
+    d_in = DevTensor.from_host(orc.scatter(np.zeros((0, 8), np.float32), orc.S0, 2), 0, 8, orc.S0)
+    d_out = DevTensor.empty(0, 8, np.float32, orc.B, 2)
+    sbp.sbp_boxing(d_in.desc, sbp.S(0), d_out.desc, sbp.B, 2)
+    sync()
+
+
+# ------------------------------------------------------------------------------- chains
+def test_config1_tiny_chain():
+    """k = 2, fp32: X[64,128] S(1) x W[128,96] S(0) -> P(sum); then P->B and P->S(0)."""
+    from workloads import CONFIGS
+    from sbp_harness import gen
+    cfg = CONFIGS["tiny"]
+    k = cfg["k"]
+    X, W = gen(cfg["X"], SEED, False), gen(cfg["W"], SEED, False)
+    Xs, Ws = orc.scatter(X, orc.S1, k), orc.scatter(W, orc.S0, k)
+    ref_parts, sy = orc.matmul_sbp(Xs, orc.S1, Ws, orc.S0)
+    assert sy == orc.P_SUM
+    dx, dw = DevTensor.from_host(Xs, 64, 128, orc.S1), DevTensor.from_host(Ws, 128, 96, orc.S0)
+    dy = DevTensor.empty(64, 96, np.float32, orc.P_SUM, k)
+    sbp.sbp_matmul(dx.desc, sbp.S(1), dw.desc, sbp.S(0), dy.desc, sbp.P_SUM, k)
+    d_b = DevTensor.empty(64, 96, np.float32, orc.B, k)
+    d_s = DevTensor.empty(64, 96, np.float32, orc.S0, k)
+    sbp.sbp_boxing(dy.desc, sbp.P_SUM, d_b.desc, sbp.B, k)
+    sbp.sbp_boxing(dy.desc, sbp.P_SUM, d_s.desc, sbp.S(0), k)
+    sync()
+    parts = dy.host()
+    for i in range(k):
+        assert_matmul_close(parts[i], ref_parts[i], 1e-5, f"partial {i}")
+    Y = orc.matmul(X, W)
+    for j, g in enumerate(d_b.host()):
+        assert_psum_close(g, ref_parts, Y, f"P->B copy {j}")
+    for j, (g, r) in enumerate(zip(d_s.host(), orc.boxing(ref_parts, orc.P_SUM, orc.S0, k))):
+        sl = slice(*orc.split_range(64, k, j))
+        assert_psum_close(g, [p[sl] for p in ref_parts], r, f"P->S(0) shard {j}")
+    # the boxing of the GPU's own partials, checked against the oracle's reduction of THOSE partials
+    rb = orc.assemble([p.astype(np.float64) for p in parts], orc.P_SUM)
+    assert_psum_close(d_b.host()[0], parts, rb, "P->B of the GPU partials")
+
+
+def test_table4_program_on_gpu():
+    """A0[4,5] S(0) x B0[5,8] B -> Y0 S(0); box to B; x B1[8,6] S(1) -> Y2 S(1); k = 2 (Table 4)."""
+    k = 2
+    A0, B0, B1 = rnd_f32(1, (4, 5)), rnd_f32(2, (5, 8)), rnd_f32(3, (8, 6))
+    d_a = DevTensor.from_host(orc.scatter(A0, orc.S0, k), 4, 5, orc.S0)
+    d_b0 = DevTensor.from_host(orc.scatter(B0, orc.B, k), 5, 8, orc.B)
+    d_b1 = DevTensor.from_host(orc.scatter(B1, orc.S1, k), 8, 6, orc.S1)
+    y0 = DevTensor.empty(4, 8, np.float32, orc.S0, k)
+    y0b = DevTensor.empty(4, 8, np.float32, orc.B, k)
+    y2 = DevTensor.empty(4, 6, np.float32, orc.S1, k)
+    sbp.sbp_matmul(d_a.desc, sbp.S(0), d_b0.desc, sbp.B, y0.desc, sbp.AUTO, k)
+    with pytest.raises(sbp.SbpError):           # Y0 as S(0) cannot feed MatMul_1: boxing is explicit
+        sbp.sbp_matmul(y0.desc, sbp.S(0), d_b1.desc, sbp.S(1), y2.desc, sbp.AUTO, k)
+    sbp.sbp_boxing(y0.desc, sbp.S(0), y0b.desc, sbp.B, k)
+    sbp.sbp_matmul(y0b.desc, sbp.B, d_b1.desc, sbp.S(1), y2.desc, sbp.S(1), k)
+    sync()
+    Y2 = orc.assemble([g.astype(np.float64) for g in y2.host()], orc.S1)
+    assert_matmul_close(Y2, orc.matmul(orc.matmul(A0, B0), B1), 1e-5, "Table 4 chain")
+
+
+def test_uvw_deferred_boxing_on_gpu():
+    """U S(1), V S(0), W B: (UV) stays P(sum) through the second matmul; one boxing at the end."""
+    k = 4
+    U, V, W = rnd_f32(1, (24, 32)), rnd_f32(2, (32, 20)), rnd_f32(3, (20, 28))
+    d_u = DevTensor.from_host(orc.scatter(U, orc.S1, k), 24, 32, orc.S1)
+    d_v = DevTensor.from_host(orc.scatter(V, orc.S0, k), 32, 20, orc.S0)
+    d_w = DevTensor.from_host(orc.scatter(W, orc.B, k), 20, 28, orc.B)
+    uv = DevTensor.empty(24, 20, np.float32, orc.P_SUM, k)
+    uvw = DevTensor.empty(24, 28, np.float32, orc.P_SUM, k)
+    out = DevTensor.empty(24, 28, np.float32, orc.B, k)
+    sbp.sbp_matmul(d_u.desc, sbp.S(1), d_v.desc, sbp.S(0), uv.desc, sbp.AUTO, k)
+    sbp.sbp_matmul(uv.desc, sbp.P_SUM, d_w.desc, sbp.B, uvw.desc, sbp.AUTO, k)
+    sbp.sbp_boxing(uvw.desc, sbp.P_SUM, out.desc, sbp.B, k)
+    sync()
+    ref = orc.matmul(orc.matmul(U, V), W)
+    for g in out.host():
+        assert_matmul_close(g, ref, 1e-4, "U.V.W with one boxing at the end")
+
+
+@pytest.mark.parametrize("k", [1, 4, 8])
+@pytest.mark.parametrize("cols", [4 * 8 * 40, 1003])
+def test_model_parallel_softmax_statistics(k, cols):
+    """bf16 logits S(1) -> local row max P(max) -> B -> local sum exp P(sum) -> B (Sec. 6.3.1)."""
+    rows = 33
+    L = rnd_bf16(7, (rows, cols), 3.0)
+    Ls = orc.scatter(L, orc.S1, k)
+    d_l = DevTensor.from_host(Ls, rows, cols, orc.S1)
+    m_p = DevTensor.empty(rows, 1, np.float32, orc.P_MAX, k)
+    m_b = DevTensor.empty(rows, 1, np.float32, orc.B, k)
+    s_p = DevTensor.empty(rows, 1, np.float32, orc.P_SUM, k)
+    s_b = DevTensor.empty(rows, 1, np.float32, orc.B, k)
+    sbp.sbp_row_max(d_l.desc, sbp.S(1), m_p.desc, k)
+    sbp.sbp_boxing(m_p.desc, sbp.P_MAX, m_b.desc, sbp.B, k)
+    sbp.sbp_row_sumexp(d_l.desc, sbp.S(1), m_b.desc, s_p.desc, k)
+    sbp.sbp_boxing(s_p.desc, sbp.P_SUM, s_b.desc, sbp.B, k)
+    sync()
+    Lv = [values(s) for s in Ls]
+    m_loc = [orc.row_max(s)[:, None] if s.shape[1] else np.full((rows, 1), -np.inf) for s in Lv]
+    for i, g in enumerate(m_p.host()):
+        assert_bits_equal(g, m_loc[i].astype(np.float32), f"local max {i}")      # bf16 values are exact in fp32
+    m = orc.boxing(m_loc, orc.P_MAX, orc.B, k)
+    for g in m_b.host():
+        assert_bits_equal(g, m[0].astype(np.float32), "global max")
+    s_loc = [orc.row_sumexp(s, m[0][:, 0])[:, None] if s.shape[1] else np.zeros((rows, 1)) for s in Lv]
+    for i, g in enumerate(s_p.host()):
+        assert np.allclose(g, s_loc[i], rtol=1e-5, atol=0), f"local sum-exp {i}"
+    s = orc.boxing(s_loc, orc.P_SUM, orc.B, k)
+    for g in s_b.host():
+        assert np.allclose(g, s[0], rtol=1e-5, atol=0)
+    for j in range(1, k):
+        assert_bits_equal(s_b.host()[j], s_b.host()[0], "denominator copies")

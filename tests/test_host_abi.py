@@ -1,0 +1,148 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+its host logic (Table 1, split geometry, argument validation) behaves as documented.  No kernel is
+launched here: every call either is host-only or must fail validation before any launch."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as orc
+import paper_2110_15032_amd as sbp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+SIG = {"S(0)": sbp.S(0), "S(1)": sbp.S(1), "B": sbp.B, "P(sum)": sbp.P_SUM, "P(max)": sbp.P_MAX}
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sbp.h")).read()
+    declared = set(re.findall(r"\b(sbp_[a-z_0-9]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    assert declared == set(sbp.EXPORTS)
+    raw = ctypes.CDLL(sbp.lib_path())
+    for name in declared:
+        assert hasattr(raw, name), f"{name} not exported"
+
+
+def test_strerror_covers_every_code():
+    seen = set()
+    for code in range(0, -11, -1):
+        msg = sbp.sbp_strerror(code)
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 11
+    assert sbp.sbp_strerror(-99) == "unknown status"
+
+
+def test_table1_through_the_abi_matches_the_printed_table():
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "table1_matmul_sbp.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    printed = {(SIG[a], SIG[b]): SIG[c] for a, b, c in rows}
+    for sx, sw in itertools.product(SIG.values(), repeat=2):
+        if (sx, sw) in printed:
+            assert sbp.sbp_infer_matmul(sx, sw) == printed[(sx, sw)]
+        else:
+            with pytest.raises(sbp.SbpError) as e:
+                sbp.sbp_infer_matmul(sx, sw)
+            assert e.value.status == -6
+    with pytest.raises(sbp.SbpError) as e:
+        sbp.sbp_infer_matmul(2, sbp.B)          # split axis 2 is not a signature of a matrix
+    assert e.value.status == -5
+
+
+@pytest.mark.parametrize("n,k", [(10, 3), (7, 8), (125000, 8), (1000000, 8), (5, 1), (0, 2)])
+def test_local_shape_uses_the_balanced_split(n, k):
+    for i in range(k):
+        b, e = orc.split_range(n, k, i)
+        assert sbp.sbp_local_shape(n, 3, sbp.S(0), k, i) == (e - b, 3)
+        assert sbp.sbp_local_shape(3, n, sbp.S(1), k, i) == (3, e - b)
+        assert sbp.sbp_local_shape(n, 3, sbp.B, k, i) == (n, 3)
+        assert sbp.sbp_local_shape(n, 3, sbp.P_SUM, k, i) == (n, 3)
+
+
+# ----------------------------------------------------------------------------- validation
+def fake(k, rows, cols, dtype=sbp.F32, base=0x10000000, step=0x1000000, trans=0):
+    """descriptor over made-up, well-aligned, non-overlapping addresses (never dereferenced:
+    every call below must be rejected before a launch)"""
+    return sbp.SbpTensor([base + i * step for i in range(k)], rows, cols, dtype, trans)
+
+
+def status_of(fn, *a, **kw):
+    with pytest.raises(sbp.SbpError) as e:
+        fn(*a, **kw)
+    return e.value.status
+
+
+def test_matmul_validation_errors():
+    k = 2
+    x = fake(k, 8, 16)
+    w = fake(k, 16, 8, base=0x20000000)
+    y = fake(k, 8, 8, base=0x30000000)
+    S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
+    st = 0  # a stream value; never used because validation fails first
+    assert status_of(sbp.sbp_matmul, x, S0, w, S1, y, sbp.AUTO, k, st) == -6          # not in Table 1
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y, B_, k, st) == -6                # would need implicit boxing
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y, P, 0, st) == -2                 # k
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y, P, 65, st) == -2
+    assert status_of(sbp.sbp_matmul, x, 7, w, S0, y, P, k, st) == -5                  # axis
+    bad_w = fake(k, 15, 8, base=0x20000000)
+    assert status_of(sbp.sbp_matmul, x, S1, bad_w, S0, y, P, k, st) == -3             # inner extents differ
+    bf_w = fake(k, 16, 8, dtype=sbp.BF16, base=0x20000000)
+    assert status_of(sbp.sbp_matmul, x, S1, bf_w, S0, y, P, k, st) == -4              # mixed input dtypes
+    y_bf = fake(k, 8, 8, dtype=sbp.BF16, base=0x30000000)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y_bf, P, k, st) == -4              # P(sum) must be f32
+    x_bf = fake(k, 8, 16, dtype=sbp.BF16)
+    assert status_of(sbp.sbp_matmul, x_bf, P, bf_w, B_, y, P, k, st) == -4            # P operand must be f32
+    y_alias = fake(k, 8, 8, base=0x10000000)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y_alias, P, k, st) == -7           # y over x
+    y_self = sbp.SbpTensor([0x30000000, 0x30000000], 8, 8, sbp.F32)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y_self, P, k, st) == -7            # two outputs, one buffer
+    y_mis = sbp.SbpTensor([0x30000000, 0x31000004], 8, 8, sbp.F32)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y_mis, P, k, st) == -8             # alignment
+    y_null = sbp.SbpTensor([0x30000000, None], 8, 8, sbp.F32)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y_null, P, k, st) == -1            # null shard
+    assert status_of(sbp.sbp_matmul_ex, x, S1, w, S0, y, P, k, st, sbp.EPI_GELU) == -6   # GeLU of a partial
+    assert status_of(sbp.sbp_matmul_ex, x, S0, fake(k, 16, 8, base=0x20000000), B_, y, S0, k, st, 7) == -9
+    y_t = fake(k, 8, 8, base=0x30000000, trans=1)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, y_t, P, k, st) == -9
+
+
+def test_boxing_validation_errors():
+    k = 2
+    a = fake(k, 8, 8)
+    b = fake(k, 8, 8, base=0x20000000)
+    st = 0
+    assert status_of(sbp.sbp_boxing, a, sbp.P_SUM, fake(k, 8, 9, base=0x20000000), sbp.B, k, st) == -3
+    assert status_of(sbp.sbp_boxing, a, sbp.P_SUM, fake(k, 8, 8, sbp.BF16, base=0x20000000), sbp.B, k, st) == -4
+    a_bf = fake(k, 8, 8, sbp.BF16)
+    b_bf = fake(k, 8, 8, sbp.BF16, base=0x20000000)
+    assert status_of(sbp.sbp_boxing, a_bf, sbp.P_SUM, b_bf, sbp.B, k, st) == -4        # P must be f32
+    assert status_of(sbp.sbp_boxing, a, sbp.P_SUM, b, sbp.P_MAX, k, st) == -6          # changes the reduction
+    assert status_of(sbp.sbp_boxing, a, sbp.S(0), a, sbp.S(1), k, st) == -7            # in place
+    assert status_of(sbp.sbp_boxing, a, 5, b, sbp.B, k, st) == -5
+    assert status_of(sbp.sbp_boxing, a, sbp.S(0), b, sbp.B, 0, st) == -2
+    # a B input may name one buffer k times
+    same = sbp.SbpTensor([0x10000000] * k, 8, 8, sbp.F32)
+    assert status_of(sbp.sbp_boxing, same, sbp.B, same, sbp.S(0), k, st) == -7         # ...but not as its own output
+
+
+def test_row_stat_validation_errors():
+    k = 4
+    L = fake(k, 16, 64, sbp.BF16)
+    out = fake(k, 16, 1, base=0x20000000)
+    gm = fake(k, 16, 1, base=0x30000000)
+    st = 0
+    assert status_of(sbp.sbp_row_max, L, sbp.B, out, k, st) == -9
+    assert status_of(sbp.sbp_row_max, L, sbp.P_SUM, out, k, st) == -6
+    assert status_of(sbp.sbp_row_max, L, sbp.S(1), fake(k, 16, 2, base=0x20000000), k, st) == -3
+    assert status_of(sbp.sbp_row_sumexp, L, sbp.S(1), fake(k, 15, 1, base=0x30000000), out, k, st) == -3
+    assert status_of(sbp.sbp_row_sumexp, L, sbp.S(1), gm, gm, k, st) == -7
+
+
+def test_knob_rejects_unknown():
+    sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, 0)
+    assert status_of(sbp.sbp_set_knob, 99, 0) == -9
+    assert status_of(sbp.sbp_set_knob, sbp.KNOB_GEMM_VARIANT, -1) == -9
