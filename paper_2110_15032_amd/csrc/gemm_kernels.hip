@@ -8,6 +8,8 @@
 //
 // Operand storage: "KC" = reduction index contiguous ([m][kk] for A, [n][kk] for B), otherwise the
 // reduction index is the slow one ([kk][m], [kk][n]).  Row-major X and W give A KC and B not-KC.
+#include <utility>
+
 #include "sbp_internal.h"
 
 namespace sbp {
@@ -70,67 +72,99 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmPlan p) {
 // ------------------------------------------------------------------------------------------------
 constexpr int BK = 64;  // reduction extent of one LDS stage, in elements (128 B per KC row)
 
-// XOR swizzle of the eight 16-byte chunks of a 128-byte KC row.  Any 8 consecutive rows land in 8
-// different chunk slots, and rows r, r + 8 differ as well, so a column of fragments read with
-// ds_read_b128 spreads over all banks whether the LDS serves 128 or 256 bytes per clock.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+// LDS image of a KC tile: row-major [R][64], the eight 16-byte chunks of a 128-byte row permuted by
+// XOR with swz(row).  8 consecutive rows use 8 different chunk slots and rows r, r + 8 differ too, so
+// the 16 rows a ds_read_b128 serves per pass cover all 64 banks (measured conflict-free on gfx950).
 __device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
+// LDS image of a not-KC tile: [64][R] with the 16-byte chunks of kk-row q permuted by XOR with
+// nswz(q): the 4 consecutive kk-rows one ds_read_b64_tr_b16 touches then sit in different bank groups.
+__device__ inline int nswz(int krow) { return (krow & 3) << 1; }
 
 template <int R, bool KC, int NT>
 struct Tile {
     static constexpr int BYTES = R * BK * 2;
     static constexpr int CHUNKS = BYTES / 16;
     static constexpr int PER_THREAD = CHUNKS / NT;
+    static constexpr int CPR = R / 8;   // 16-byte chunks per kk-row of a not-KC tile
     static_assert(CHUNKS % NT == 0, "tile must divide over the workgroup");
+    static_assert(KC || CPR >= 8, "not-KC swizzle needs at least 8 chunks per row");
 
-    // global -> registers.  first = first tile row (m or n index), limit = extent of that index.
-    __device__ static void fetch(u32x4 (&reg)[PER_THREAD], const uint16_t* base, int ld, int first, int limit,
-                                 int k0, int tid) {
-#pragma unroll
-        for (int it = 0; it < PER_THREAD; ++it) {
-            const int q = tid + it * NT;
-            const uint16_t* ptr;
-            if constexpr (KC) {
-                int row = first + (q >> 3);
-                row = row < limit ? row : limit - 1;                 // clamped rows are never stored
-                ptr = base + (int64_t)row * ld + k0 + (q & 7) * 8;
-            } else {
-                constexpr int CPR = R / 8;                           // chunks per kk-row
-                int col = first + (q % CPR) * 8;
-                col = col < limit ? col : limit - 8;
-                ptr = base + (int64_t)(k0 + q / CPR) * ld + col;
-            }
-            reg[it] = *reinterpret_cast<const u32x4*>(ptr);
-        }
-    }
-    // registers -> LDS
-    __device__ static void stash(const u32x4 (&reg)[PER_THREAD], char* lds, int tid) {
-#pragma unroll
-        for (int it = 0; it < PER_THREAD; ++it) {
-            const int q = tid + it * NT;
-            int off;
-            if constexpr (KC) {
-                const int row = q >> 3;
-                off = row * 128 + (((q & 7) ^ swz(row)) << 4);
-            } else {
-                off = q * 16;                                        // [kk][R] dense
-            }
-            *reinterpret_cast<u32x4*>(lds + off) = reg[it];
-        }
-    }
-    // LDS -> one MFMA operand: 8 consecutive kk (16 s + 8 (lane / 32) ...) for index `row`
-    __device__ static bf16x8 frag(const char* lds, int row, int s, int lane) {
-        const int kh = lane >> 5;
+    // Byte offset (from the operand's base, at reduction offset 0) of the 16 bytes that belong in
+    // LDS chunk position p.  first = first tile row (m or n), limit = extent of that index; rows or
+    // columns past the limit are clamped to valid memory and never reach an output.
+    __device__ static uint32_t src_offset(int ld, int first, int limit, int p) {
         if constexpr (KC) {
-            return *reinterpret_cast<const bf16x8*>(lds + row * 128 + (((2 * s + kh) ^ swz(row)) << 4));
+            const int row = p >> 3;
+            int g = first + row;
+            g = g < limit ? g : limit - 1;
+            return ((uint32_t)g * (uint32_t)ld + (uint32_t)(((p & 7) ^ swz(row)) * 8)) * 2u;
         } else {
-            const uint16_t* t = reinterpret_cast<const uint16_t*>(lds) + (16 * s + 8 * kh) * R + row;
-            u16x8 v;
+            const int krow = p / CPR;
+            int col = first + (((p % CPR) ^ nswz(krow)) * 8);
+            col = col < limit ? col : limit - 8;
+            return ((uint32_t)krow * (uint32_t)ld + (uint32_t)col) * 2u;
+        }
+    }
+    // bytes to advance the source by for one BK step
+    __device__ static uint32_t step_bytes(int ld) { return KC ? BK * 2u : (uint32_t)ld * BK * 2u; }
+
+    // global -> LDS without passing through registers: each lane's 16 bytes land at
+    // lds + 16 * (p0 + lane), p0 uniform per wave instruction.
+    __device__ static void load_direct(char* lds_tile, const char* src, const uint32_t (&off)[PER_THREAD], int tid) {
+        const int wave = tid >> 6;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = t[j * R];
+        for (int it = 0; it < PER_THREAD; ++it) {
+            const int p0 = it * NT + wave * 64;
+            __builtin_amdgcn_global_load_lds((gbl_void*)(src + off[it]), (lds_void*)(lds_tile + p0 * 16), 16, 0, 0);
+        }
+    }
+    // global -> registers -> LDS (same LDS image)
+    __device__ static void fetch(u32x4 (&reg)[PER_THREAD], const char* src, const uint32_t (&off)[PER_THREAD]) {
+#pragma unroll
+        for (int it = 0; it < PER_THREAD; ++it) reg[it] = *reinterpret_cast<const u32x4*>(src + off[it]);
+    }
+    __device__ static void stash(const u32x4 (&reg)[PER_THREAD], char* lds_tile, int tid) {
+#pragma unroll
+        for (int it = 0; it < PER_THREAD; ++it) *reinterpret_cast<u32x4*>(lds_tile + (it * NT + tid) * 16) = reg[it];
+    }
+
+    // LDS -> one 32x32x16 MFMA operand for tile rows base .. base + 31 (base a multiple of 32):
+    // lane l gets the 8 values kk = 16 ks + 8 (l / 32) + 0..7 of row base + l % 32.
+    __device__ static bf16x8 frag(const char* lds_tile, int base, int ks, int lane) {
+        if constexpr (KC) {
+            const int row = base + (lane & 31);
+            return *reinterpret_cast<const bf16x8*>(lds_tile + row * 128 + (((2 * ks + (lane >> 5)) ^ swz(row)) << 4));
+        } else {
+            // ds_read_b64_tr_b16: in each group of 16 lanes, lane s supplies the address of 4
+            // consecutive elements (row s / 4, element group s % 4) of a 4 x 16 block and receives
+            // column s of it.  Two reads give the 8 kk values.
+            const int s = lane & 15, nh = (lane >> 4) & 1, kh = lane >> 5;
+            const int krow = 16 * ks + 8 * kh + (s >> 2);
+            const int chunk = (base >> 3) + 2 * nh + ((s & 3) >> 1);
+            const int within = (s & 1) * 8;
+            const char* a0 = lds_tile + krow * (R * 2) + ((chunk ^ nswz(krow)) << 4) + within;
+            const char* a1 = a0 + 4 * (R * 2);   // rows krow + 4: same krow & 3, same swizzle
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8, v);
         }
     }
 };
+
+template <int N, typename F, int... Is>
+__device__ inline void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ inline void static_for(F&& f) {
+    static_for_impl<N>(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
 
 struct TileCoord {
     int g, tile_m, tile_n;
@@ -159,15 +193,57 @@ __device__ inline TileCoord map_tile(int bid, int nblk, int tm, int tn, int grou
     return t;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, typename OutT>
+// erfc(z) for z >= 0 as t * exp(-z^2 + P(t)), t = 1 / (1 + z / 2): the Chebyshev fit published in
+// Numerical Recipes ("erfcc"), fractional error below 1.2e-7 for every z, so the negative tail of
+// GeLU keeps its relative accuracy.  Branch-free: one rcp, one exp, ten FMAs.
+__device__ inline float erfc_pos(float z) {
+    const float t = __frcp_rn(1.0f + 0.5f * z);
+    float p = 0.17087277f;
+    p = fmaf(p, t, -0.82215223f);
+    p = fmaf(p, t, 1.48851587f);
+    p = fmaf(p, t, -1.13520398f);
+    p = fmaf(p, t, 0.27886807f);
+    p = fmaf(p, t, -0.18628806f);
+    p = fmaf(p, t, 0.09678418f);
+    p = fmaf(p, t, 0.37409196f);
+    p = fmaf(p, t, 1.00002368f);
+    p = fmaf(p, t, -1.26551223f);
+    return t * __expf(fmaf(-z, z, p));
+}
+// gelu(x) = 0.5 x erfc(-x / sqrt 2)
+__device__ inline float gelu_fast(float x) {
+    const float z = x * -0.70710678118654752f;
+    const float e = erfc_pos(fabsf(z));
+    return 0.5f * x * (z >= 0.0f ? e : 2.0f - e);
+}
+
+template <int EPI>
+__device__ inline float mfma_epilogue(float v) {
+    if constexpr (EPI == SBP_EPI_GELU) return gelu_fast(v);
+    else return v;
+}
+
+// LOAD: 0 = global -> LDS directly (global_load_lds_dwordx4), 1 = through registers.
+//
+// Schedule of one reduction step t (LDS stage t & 1 holds tile t):
+//   issue the loads of tile t + 1 into the other stage        (it was last read in step t - 1)
+//   ks = 0..2: read the fragments of ks + 1, run the 16 MFMAs of ks
+//   wait for this wave's loads, workgroup barrier             (tile t + 1 complete, stage t & 1 free)
+//   read the fragments of (t + 1, ks = 0), run the MFMAs of (t, ks = 3) underneath that latency
+// The four stages are separate __shared__ objects on purpose: the compiler then knows that a
+// direct-to-LDS load into one stage cannot alias the fragment reads of the other and does not
+// serialise them with a vmcnt wait.
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int LOAD, int EPI, typename OutT>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int tm, int tn) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
     constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wave
     using TA = Tile<BM, A_KC, NT>;
     using TB = Tile<BN, B_KC, NT>;
-    constexpr int STAGE = TA::BYTES + TB::BYTES;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
 
     const TileCoord tc = map_tile(blockIdx.x, gridDim.x, tm, tn, p.groups);
     if (!tc.valid) return;
@@ -177,8 +253,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const uint16_t* A = static_cast<const uint16_t*>(s.a);
-    const uint16_t* B = static_cast<const uint16_t*>(s.b);
+    const char* A = static_cast<const char*>(s.a);
+    const char* B = static_cast<const char*>(s.b);
+
+    uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+#pragma unroll
+    for (int it = 0; it < TA::PER_THREAD; ++it) offa[it] = TA::src_offset(s.lda, m0, s.m, it * NT + tid);
+#pragma unroll
+    for (int it = 0; it < TB::PER_THREAD; ++it) offb[it] = TB::src_offset(s.ldb, n0, s.n, it * NT + tid);
+    const uint32_t stepa = TA::step_bytes(s.lda), stepb = TB::step_bytes(s.ldb);
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -188,92 +271,126 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    u32x4 ra[TA::PER_THREAD], rb[TB::PER_THREAD];
-    const int steps = s.kk / BK;
-    TA::fetch(ra, A, s.lda, m0, s.m, 0, tid);
-    TB::fetch(rb, B, s.ldb, n0, s.n, 0, tid);
-    TA::stash(ra, smem, tid);
-    TB::stash(rb, smem + TA::BYTES, tid);
-    __syncthreads();
+    bf16x8 fa[2][FM], fb[2][FN];
+    u32x4 ra[LOAD == 1 ? TA::PER_THREAD : 1], rb[LOAD == 1 ? TB::PER_THREAD : 1];
 
-    for (int t = 0; t < steps; ++t) {
-        const char* sa = smem + (t & 1) * STAGE;
-        const char* sb = sa + TA::BYTES;
-        if (t + 1 < steps) {
-            TA::fetch(ra, A, s.lda, m0, s.m, (t + 1) * BK, tid);
-            TB::fetch(rb, B, s.ldb, n0, s.n, (t + 1) * BK, tid);
+    auto read_frags = [&](const char* sa, const char* sb, int ks, int slot) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[slot][i] = TA::frag(sa, wm * TM + i * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, wn * TN + j * 32, ks, lane);
+    };
+    auto mfmas = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+    };
+    // one reduction step computing from stage CUR; `more` = another tile follows
+    auto step = [&](auto cur, bool more) {
+        constexpr int CUR = decltype(cur)::value;
+        const char* sa = CUR ? sA1 : sA0;
+        const char* sb = CUR ? sB1 : sB0;
+        char* da = CUR ? sA0 : sA1;
+        char* db = CUR ? sB0 : sB1;
+        if (more) {
+            if constexpr (LOAD == 0) {
+                TA::load_direct(da, A, offa, tid);
+                TB::load_direct(db, B, offb, tid);
+            } else {
+                TA::fetch(ra, A, offa);
+                TB::fetch(rb, B, offb);
+            }
+            A += stepa;
+            B += stepb;
         }
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[FM], fb[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) fa[i] = TA::frag(sa, wm * TM + i * 32 + (lane & 31), ks, lane);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) fb[j] = TB::frag(sb, wn * TN + j * 32 + (lane & 31), ks, lane);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+            read_frags(sa, sb, ks + 1, (ks + 1) & 1);
+            mfmas(ks & 1);
         }
-        if (t + 1 < steps) {
-            char* da = smem + ((t + 1) & 1) * STAGE;
-            TA::stash(ra, da, tid);
-            TB::stash(rb, da + TA::BYTES, tid);
-        }
-        __syncthreads();
-    }
-
-    // D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r]
-    OutT* C = static_cast<OutT*>(s.c);
-    const int cn = lane & 31, rm = 4 * (lane >> 5);
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int n = n0 + wn * TN + j * 32 + cn;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * TM + i * 32 + 8 * (r >> 2) + rm + (r & 3);
-                if (m < s.m && n < s.n) store_out(C, (int64_t)m * s.ldc + n, epilogue<EPI>(acc[i][j][r]));
+        if constexpr (LOAD == 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            if (more) {
+                TA::stash(ra, da, tid);
+                TB::stash(rb, db, tid);
             }
         }
+        __syncthreads();
+        if (more) read_frags(da, db, 0, 0);
+        mfmas((BK / 16 - 1) & 1);
+    };
+
+    const int steps = s.kk / BK;
+    if constexpr (LOAD == 0) {
+        TA::load_direct(sA0, A, offa, tid);
+        TB::load_direct(sB0, B, offb, tid);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        TA::fetch(ra, A, offa);
+        TB::fetch(rb, B, offb);
+        TA::stash(ra, sA0, tid);
+        TB::stash(rb, sB0, tid);
+    }
+    A += stepa;
+    B += stepb;
+    __syncthreads();
+    read_frags(sA0, sB0, 0, 0);
+    int t = 0;
+    for (; t + 2 <= steps; t += 2) {
+        step(std::integral_constant<int, 0>{}, true);
+        step(std::integral_constant<int, 1>{}, t + 2 < steps);
+    }
+    if (t < steps) step(std::integral_constant<int, 0>{}, false);
+
+    // D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r].  Compile-time tile indices: the
+    // accumulators must never be indexed dynamically (they would move to scratch memory).
+    OutT* C = static_cast<OutT*>(s.c);
+    const int cn = lane & 31, rm = 4 * (lane >> 5);
+    static_for<FM * FN>([&](auto idx) {
+        constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
+        const int n = n0 + wn * TN + j * 32 + cn;
+        const int mb = m0 + wm * TM + i * 32 + rm;
+        static_for<16>([&](auto ridx) {
+            constexpr int r = decltype(ridx)::value;
+            const int m = mb + 8 * (r >> 2) + (r & 3);
+            const float v = mfma_epilogue<EPI>(acc[i][j][r]);
+            if (m < s.m && n < s.n) store_out(C, (int64_t)m * s.ldc + n, v);
+        });
+    });
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int EPI, typename OutT>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int LOAD, int EPI, typename OutT>
 int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, EPI, OutT>;
-    constexpr int smem = 2 * (BM + BN) * BK * 2;
-    static bool attr_set = false;   // benign race: the call is idempotent
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return SBP_ERR_LAUNCH;
-        attr_set = true;
-    }
+    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, LOAD, EPI, OutT>;
     const int tm = (max_m + BM - 1) / BM, tn = (max_n + BN - 1) / BN;
     const int64_t tiles = (int64_t)tm * tn * plan.groups;
     const int64_t nblk = (tiles + 7) / 8 * 8;
     if (nblk > 0x7FFFFFFF) return SBP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), smem, st, plan, tm, tn);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn);
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, typename OutT>
+template <int BM, int BN, int WM, int WN, int LOAD, int EPI, typename OutT>
 int32_t launch_mfma_layout(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    if (plan.a_kc && plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, true, EPI, OutT>(plan, max_m, max_n, st);
-    if (plan.a_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, EPI, OutT>(plan, max_m, max_n, st);
-    if (plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, false, true, EPI, OutT>(plan, max_m, max_n, st);
-    return launch_mfma_cfg<BM, BN, WM, WN, false, false, EPI, OutT>(plan, max_m, max_n, st);
+    if (plan.a_kc && plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, true, LOAD, EPI, OutT>(plan, max_m, max_n, st);
+    if (plan.a_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, LOAD, EPI, OutT>(plan, max_m, max_n, st);
+    if (plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, false, true, LOAD, EPI, OutT>(plan, max_m, max_n, st);
+    return launch_mfma_cfg<BM, BN, WM, WN, false, false, LOAD, EPI, OutT>(plan, max_m, max_n, st);
 }
 
-template <int BM, int BN, int WM, int WN>
+// fp32 results carry no epilogue on this path (GeLU of a P(sum) partial is rejected upstream and
+// fp32 inputs take the generic kernel), so three (epilogue, output) pairs cover every request.
+template <int BM, int BN, int WM, int WN, int LOAD>
 int32_t launch_mfma_out(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
     if (plan.out_dtype == SBP_F32) {
-        if (plan.epilogue == SBP_EPI_GELU) return launch_mfma_layout<BM, BN, WM, WN, SBP_EPI_GELU, float>(plan, max_m, max_n, st);
-        return launch_mfma_layout<BM, BN, WM, WN, SBP_EPI_NONE, float>(plan, max_m, max_n, st);
+        if (plan.epilogue != SBP_EPI_NONE) return SBP_ERR_UNSUPPORTED;
+        return launch_mfma_layout<BM, BN, WM, WN, LOAD, SBP_EPI_NONE, float>(plan, max_m, max_n, st);
     }
-    if (plan.epilogue == SBP_EPI_GELU) return launch_mfma_layout<BM, BN, WM, WN, SBP_EPI_GELU, uint16_t>(plan, max_m, max_n, st);
-    return launch_mfma_layout<BM, BN, WM, WN, SBP_EPI_NONE, uint16_t>(plan, max_m, max_n, st);
+    if (plan.epilogue == SBP_EPI_GELU) return launch_mfma_layout<BM, BN, WM, WN, LOAD, SBP_EPI_GELU, uint16_t>(plan, max_m, max_n, st);
+    return launch_mfma_layout<BM, BN, WM, WN, LOAD, SBP_EPI_NONE, uint16_t>(plan, max_m, max_n, st);
 }
 
 template <bool IN_BF16, typename OutT>
@@ -294,6 +411,10 @@ bool mfma_ok(const GemmPlan& plan) {
         if (s.lda % 8 || s.ldb % 8) return false;
         if (!plan.a_kc && s.m < 8) return false;
         if (!plan.b_kc && s.n < 8) return false;
+        // source offsets are 32-bit byte offsets from the shard base
+        const int64_t ea = plan.a_kc ? (int64_t)s.m * s.lda : (int64_t)s.kk * s.lda;
+        const int64_t eb = plan.b_kc ? (int64_t)s.n * s.ldb : (int64_t)s.kk * s.ldb;
+        if (ea * 2 >= ((int64_t)1 << 32) || eb * 2 >= ((int64_t)1 << 32)) return false;
     }
     return true;
 }
@@ -325,9 +446,11 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
     }
     switch (variant) {
         case 0:
-        case 2: return launch_mfma_out<256, 256, 2, 2>(plan, max_m, max_n, stream);
-        case 3: return launch_mfma_out<256, 256, 2, 4>(plan, max_m, max_n, stream);
-        case 4: return launch_mfma_out<128, 128, 2, 2>(plan, max_m, max_n, stream);
+        case 2: return launch_mfma_out<256, 256, 2, 2, 0>(plan, max_m, max_n, stream);
+        case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
+        case 4: return launch_mfma_out<128, 128, 2, 2, 0>(plan, max_m, max_n, stream);
+        case 5: return launch_mfma_out<256, 256, 2, 2, 1>(plan, max_m, max_n, stream);
+        case 6: return launch_mfma_out<256, 256, 2, 4, 1>(plan, max_m, max_n, stream);
         default: return SBP_ERR_UNSUPPORTED;
     }
 }
