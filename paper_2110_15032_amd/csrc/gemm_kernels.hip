@@ -4,7 +4,8 @@
 //   gemm_generic_kernel   any dtype / shape / pitch, one output element per lane, fp32 FMA chain.
 //                         Used for fp32 operands and for shapes the MFMA path does not take.
 //   gemm_mfma_kernel      bf16 x bf16 -> fp32 on the matrix cores (v_mfma_f32_32x32x16_bf16),
-//                         BM x BN x 64 macro-tile per workgroup, double-buffered LDS.
+//                         BM x BN x 64 macro-tile per workgroup, global->LDS loads that bypass
+//                         registers, double-buffered LDS.
 //
 // Operand storage: "KC" = reduction index contiguous ([m][kk] for A, [n][kk] for B), otherwise the
 // reduction index is the slow one ([kk][m], [kk][n]).  Row-major X and W give A KC and B not-KC.
@@ -75,14 +76,17 @@ constexpr int BK = 64;  // reduction extent of one LDS stage, in elements (128 B
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
+typedef __attribute__((address_space(1))) const char gbl_char;
 
 // LDS image of a KC tile: row-major [R][64], the eight 16-byte chunks of a 128-byte row permuted by
 // XOR with swz(row).  8 consecutive rows use 8 different chunk slots and rows r, r + 8 differ too, so
 // the 16 rows a ds_read_b128 serves per pass cover all 64 banks (measured conflict-free on gfx950).
 __device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
 // LDS image of a not-KC tile: [64][R] with the 16-byte chunks of kk-row q permuted by XOR with
-// nswz(q): the 4 consecutive kk-rows one ds_read_b64_tr_b16 touches then sit in different bank groups.
-__device__ inline int nswz(int krow) { return (krow & 3) << 1; }
+// nswz(q).  A ds_read_b64_tr_b16 serves 32 lanes per pass: 4 consecutive kk-rows x 64 contiguous
+// bytes.  Row pitch is a multiple of 256 B, so without the permutation the 4 rows share banks;
+// moving row q by (q % 4) * 64 B spreads them over all 64 banks.
+__device__ inline int nswz(int krow) { return (krow & 3) << 2; }
 
 template <int R, bool KC, int NT>
 struct Tile {
@@ -91,7 +95,7 @@ struct Tile {
     static constexpr int PER_THREAD = CHUNKS / NT;
     static constexpr int CPR = R / 8;   // 16-byte chunks per kk-row of a not-KC tile
     static_assert(CHUNKS % NT == 0, "tile must divide over the workgroup");
-    static_assert(KC || CPR >= 8, "not-KC swizzle needs at least 8 chunks per row");
+    static_assert(KC || CPR >= 16, "not-KC swizzle needs at least 16 chunks per row");
 
     // Byte offset (from the operand's base, at reduction offset 0) of the 16 bytes that belong in
     // LDS chunk position p.  first = first tile row (m or n), limit = extent of that index; rows or
@@ -113,45 +117,61 @@ struct Tile {
     __device__ static uint32_t step_bytes(int ld) { return KC ? BK * 2u : (uint32_t)ld * BK * 2u; }
 
     // global -> LDS without passing through registers: each lane's 16 bytes land at
-    // lds + 16 * (p0 + lane), p0 uniform per wave instruction.
-    __device__ static void load_direct(char* lds_tile, const char* src, const uint32_t (&off)[PER_THREAD], int tid) {
-        const int wave = tid >> 6;
+    // lds + 16 * (p0 + lane), p0 uniform per wave instruction (wave must be a uniform value).
+    // src is a uniform global-address-space base, off the per-lane 32-bit byte offsets.
+    __device__ static void load_direct(char* lds_tile, gbl_char* src, const uint32_t (&off)[PER_THREAD], int wave) {
 #pragma unroll
         for (int it = 0; it < PER_THREAD; ++it) {
             const int p0 = it * NT + wave * 64;
             __builtin_amdgcn_global_load_lds((gbl_void*)(src + off[it]), (lds_void*)(lds_tile + p0 * 16), 16, 0, 0);
         }
     }
-    // global -> registers -> LDS (same LDS image)
-    __device__ static void fetch(u32x4 (&reg)[PER_THREAD], const char* src, const uint32_t (&off)[PER_THREAD]) {
-#pragma unroll
-        for (int it = 0; it < PER_THREAD; ++it) reg[it] = *reinterpret_cast<const u32x4*>(src + off[it]);
-    }
-    __device__ static void stash(const u32x4 (&reg)[PER_THREAD], char* lds_tile, int tid) {
-#pragma unroll
-        for (int it = 0; it < PER_THREAD; ++it) *reinterpret_cast<u32x4*>(lds_tile + (it * NT + tid) * 16) = reg[it];
-    }
 
     // LDS -> one 32x32x16 MFMA operand for tile rows base .. base + 31 (base a multiple of 32):
     // lane l gets the 8 values kk = 16 ks + 8 (l / 32) + 0..7 of row base + l % 32.
-    __device__ static bf16x8 frag(const char* lds_tile, int base, int ks, int lane) {
+    // Fragment addressing.  The compiler tags an LDS access with the __shared__ object it touches
+    // only through SHORT pointer chains, and it needs that tag to see that fragment reads of one
+    // stage cannot alias direct-to-LDS loads into another (otherwise it serialises them with a
+    // vmcnt wait).  So every address is tile + (lane offset + constant): the lane offsets are
+    // computed once, made opaque to reassociation, and everything else folds into the instruction's
+    // immediate offset.  A KC tile needs one lane offset per ks (the swizzle XORs ks into the chunk
+    // index), a not-KC tile one per 32-wide block (the swizzle XORs the block index).
+    template <int F>
+    static constexpr int nlo() { return KC ? BK / 16 : F; }
+
+    __device__ static int lane_offset(int idx, int wave_base, int lane) {
+        int off;
+        if constexpr (KC) {   // idx = ks; block i adds i * 32 * 128
+            const int row = wave_base + (lane & 31);
+            off = row * 128 + (((2 * idx + (lane >> 5)) ^ swz(row)) << 4);
+        } else {              // idx = block; ks adds 16 ks * R * 2, the second read 4 * R * 2
+            const int s = lane & 15, nh = (lane >> 4) & 1, kh = lane >> 5;
+            const int krow = 8 * kh + (s >> 2);
+            const int chunk = ((wave_base + 32 * idx) >> 3) + 2 * nh + ((s & 3) >> 1);
+            off = krow * (R * 2) + ((chunk ^ nswz(krow)) << 4) + (s & 1) * 8;
+        }
+        asm("" : "+v"(off));   // opaque: keep it one addend
+        return off;
+    }
+
+    // LDS -> one 32x32x16 MFMA operand for 32-row block blk of the wave tile: lane l gets the 8 values
+    // kk = 16 ks + 8 (l / 32) + 0..7 of row (block base + l % 32).
+    template <int NLO>
+    __device__ static bf16x8 frag(const char* lds_tile, const int (&lo)[NLO], int blk, int ks) {
         if constexpr (KC) {
-            const int row = base + (lane & 31);
-            return *reinterpret_cast<const bf16x8*>(lds_tile + row * 128 + (((2 * ks + (lane >> 5)) ^ swz(row)) << 4));
+            // swz(row + 32 blk) differs from swz(row) by (4 blk) & 7: odd blocks flip chunk bit 2
+            const int off = (lo[ks] ^ ((blk & 1) << 6)) + blk * 32 * 128;
+            return *reinterpret_cast<const bf16x8*>(lds_tile + off);
         } else {
             // ds_read_b64_tr_b16: in each group of 16 lanes, lane s supplies the address of 4
             // consecutive elements (row s / 4, element group s % 4) of a 4 x 16 block and receives
-            // column s of it.  Two reads give the 8 kk values.
-            const int s = lane & 15, nh = (lane >> 4) & 1, kh = lane >> 5;
-            const int krow = 16 * ks + 8 * kh + (s >> 2);
-            const int chunk = (base >> 3) + 2 * nh + ((s & 3) >> 1);
-            const int within = (s & 1) * 8;
-            const char* a0 = lds_tile + krow * (R * 2) + ((chunk ^ nswz(krow)) << 4) + within;
-            const char* a1 = a0 + 4 * (R * 2);   // rows krow + 4: same krow & 3, same swizzle
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a1));
+            // column s of it.  Two reads (kk-rows +0..3 and +4..7, same swizzle) give the 8 values.
+            const int off0 = lo[blk] + ks * 16 * (R * 2);
+            const int off1 = off0 + 4 * (R * 2);
+            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off0));
+            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off1));
             typedef short s16x8 __attribute__((ext_vector_type(8)));
-            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const s16x8 v = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8, v);
         }
     }
@@ -223,23 +243,39 @@ __device__ inline float mfma_epilogue(float v) {
     else return v;
 }
 
-// LOAD: 0 = global -> LDS directly (global_load_lds_dwordx4), 1 = through registers.
-//
+// Scheduling hint for one phase of NMFMA matrix instructions: let one LDS read and (for the first NVM
+// of them) one global->LDS load issue behind each MFMA, so that the operands of the NEXT phase stream
+// in underneath the matrix pipe instead of in a burst right before they are needed.
+template <int NMFMA, int NDS, int NVM>
+__device__ inline void pace() {
+    static_for<NMFMA>([&](auto i) {
+        constexpr int I = decltype(i)::value;
+        constexpr int nds = NDS * (I + 1) / NMFMA - NDS * I / NMFMA;   // spread evenly, all before the phase ends
+        constexpr int nvm = NVM * (I + 1) / NMFMA - NVM * I / NMFMA;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // 1 MFMA
+        if constexpr (nds > 0) __builtin_amdgcn_sched_group_barrier(0x100, nds, 0);   // LDS reads
+        if constexpr (nvm > 0) __builtin_amdgcn_sched_group_barrier(0x010, nvm, 0);   // VMEM
+    });
+}
+
 // Schedule of one reduction step t (LDS stage t & 1 holds tile t):
-//   issue the loads of tile t + 1 into the other stage        (it was last read in step t - 1)
-//   ks = 0..2: read the fragments of ks + 1, run the 16 MFMAs of ks
-//   wait for this wave's loads, workgroup barrier             (tile t + 1 complete, stage t & 1 free)
-//   read the fragments of (t + 1, ks = 0), run the MFMAs of (t, ks = 3) underneath that latency
+//   phase 0..2: issue the direct-to-LDS loads of tile t + 1 into the other stage (phase 0 only;
+//               that stage was last read in step t - 1), read the fragments of ks + 1, run the
+//               MFMAs of ks
+//   wait for this wave's loads, workgroup barrier      (tile t + 1 complete, stage t & 1 free)
+//   phase 3:    read the fragments of (t + 1, ks = 0) underneath the MFMAs of (t, ks = 3)
 // The four stages are separate __shared__ objects on purpose: the compiler then knows that a
 // direct-to-LDS load into one stage cannot alias the fragment reads of the other and does not
 // serialise them with a vmcnt wait.
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int LOAD, int EPI, typename OutT>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int tm, int tn) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;   // wave tile
     constexpr int FM = TM / 32, FN = TN / 32;   // 32x32 MFMA tiles per wave
+    constexpr int NDS = (A_KC ? FM : 2 * FM) + (B_KC ? FN : 2 * FN);   // LDS reads per phase
     using TA = Tile<BM, A_KC, NT>;
     using TB = Tile<BN, B_KC, NT>;
+    constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;                // loads per step
     __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
     __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
     __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
@@ -251,10 +287,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
     const int m0 = tc.tile_m * BM, n0 = tc.tile_n * BN;
     if (m0 >= s.m || n0 >= s.n) return;   // uneven shards: this one has fewer tiles
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const char* A = static_cast<const char*>(s.a);
-    const char* B = static_cast<const char*>(s.b);
+    gbl_char* A = (gbl_char*)s.a;
+    gbl_char* B = (gbl_char*)s.b;
 
     uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
 #pragma unroll
@@ -272,13 +309,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     bf16x8 fa[2][FM], fb[2][FN];
-    u32x4 ra[LOAD == 1 ? TA::PER_THREAD : 1], rb[LOAD == 1 ? TB::PER_THREAD : 1];
+    int loa[TA::template nlo<FM>()], lob[TB::template nlo<FN>()];
+#pragma unroll
+    for (int x = 0; x < TA::template nlo<FM>(); ++x) loa[x] = TA::lane_offset(x, wm * TM, lane);
+#pragma unroll
+    for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
 
     auto read_frags = [&](const char* sa, const char* sb, int ks, int slot) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) fa[slot][i] = TA::frag(sa, wm * TM + i * 32, ks, lane);
+        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, lob, j, ks);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, wn * TN + j * 32, ks, lane);
+        for (int i = 0; i < FM; ++i) fa[slot][i] = TA::frag(sa, loa, i, ks);
     };
     auto mfmas = [&](int slot) {
 #pragma unroll
@@ -287,84 +328,86 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
             for (int j = 0; j < FN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
     };
-    // one reduction step computing from stage CUR; `more` = another tile follows
-    auto step = [&](auto cur, bool more) {
+    // One reduction step computing from stage CUR.  It is branch-free so that the whole step is one
+    // scheduling region: the loads of the next tile are ALWAYS issued (after the last tile the source
+    // simply stops advancing, so the reload stays in bounds and nobody reads it) and the fragments of
+    // the next stage are always read.
+    const int steps = s.kk / BK;
+    int t = 0;
+    auto step = [&](auto cur) {
         constexpr int CUR = decltype(cur)::value;
         const char* sa = CUR ? sA1 : sA0;
         const char* sb = CUR ? sB1 : sB0;
         char* da = CUR ? sA0 : sA1;
         char* db = CUR ? sB0 : sB1;
-        if (more) {
-            if constexpr (LOAD == 0) {
-                TA::load_direct(da, A, offa, tid);
-                TB::load_direct(db, B, offb, tid);
-            } else {
-                TA::fetch(ra, A, offa);
-                TB::fetch(rb, B, offb);
-            }
-            A += stepa;
-            B += stepb;
-        }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16 - 1; ++ks) {
-            read_frags(sa, sb, ks + 1, (ks + 1) & 1);
-            mfmas(ks & 1);
-        }
-        if constexpr (LOAD == 0) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        } else {
-            if (more) {
-                TA::stash(ra, da, tid);
-                TB::stash(rb, db, tid);
-            }
-        }
+        TA::load_direct(da, A, offa, wave);
+        TB::load_direct(db, B, offb, wave);
+        ++t;
+        const bool adv = t + 1 < steps;      // tile t + 1 exists (t already counts this step)
+        A += adv ? stepa : 0u;
+        B += adv ? stepb : 0u;
+        read_frags(sa, sb, 1, 1);
+        mfmas(0);
+        pace<FM * FN, NDS, NVM>();
+        read_frags(sa, sb, 2, 0);
+        mfmas(1);
+        pace<FM * FN, NDS, 0>();
+        read_frags(sa, sb, 3, 1);
+        mfmas(0);
+        pace<FM * FN, NDS, 0>();
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's direct-to-LDS loads have landed
         __syncthreads();
-        if (more) read_frags(da, db, 0, 0);
-        mfmas((BK / 16 - 1) & 1);
+        read_frags(da, db, 0, 0);
+        mfmas(1);
+        pace<FM * FN, NDS, 0>();
     };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
 
-    const int steps = s.kk / BK;
-    if constexpr (LOAD == 0) {
-        TA::load_direct(sA0, A, offa, tid);
-        TB::load_direct(sB0, B, offb, tid);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else {
-        TA::fetch(ra, A, offa);
-        TB::fetch(rb, B, offb);
-        TA::stash(ra, sA0, tid);
-        TB::stash(rb, sB0, tid);
+    TA::load_direct(sA0, A, offa, wave);
+    TB::load_direct(sB0, B, offb, wave);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (steps > 1) {
+        A += stepa;
+        B += stepb;
     }
-    A += stepa;
-    B += stepb;
     __syncthreads();
     read_frags(sA0, sB0, 0, 0);
-    int t = 0;
-    for (; t + 2 <= steps; t += 2) {
-        step(std::integral_constant<int, 0>{}, true);
-        step(std::integral_constant<int, 1>{}, t + 2 < steps);
+    for (int pair = 0; pair < steps / 2; ++pair) {
+        step(I0{});
+        step(I1{});
     }
-    if (t < steps) step(std::integral_constant<int, 0>{}, false);
+    if (steps & 1) step(I0{});
 
     // D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r].  Compile-time tile indices: the
     // accumulators must never be indexed dynamically (they would move to scratch memory).
     OutT* C = static_cast<OutT*>(s.c);
     const int cn = lane & 31, rm = 4 * (lane >> 5);
+    const bool whole = m0 + BM <= s.m && n0 + BN <= s.n;   // uniform: interior tiles store unguarded
     static_for<FM * FN>([&](auto idx) {
         constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
         const int n = n0 + wn * TN + j * 32 + cn;
         const int mb = m0 + wm * TM + i * 32 + rm;
-        static_for<16>([&](auto ridx) {
-            constexpr int r = decltype(ridx)::value;
-            const int m = mb + 8 * (r >> 2) + (r & 3);
-            const float v = mfma_epilogue<EPI>(acc[i][j][r]);
-            if (m < s.m && n < s.n) store_out(C, (int64_t)m * s.ldc + n, v);
-        });
+        OutT* cp = C + (int64_t)mb * s.ldc + n;
+        if (whole) {
+            static_for<16>([&](auto ridx) {
+                constexpr int r = decltype(ridx)::value;
+                store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, mfma_epilogue<EPI>(acc[i][j][r]));
+            });
+        } else {
+            static_for<16>([&](auto ridx) {
+                constexpr int r = decltype(ridx)::value;
+                const int m = mb + 8 * (r >> 2) + (r & 3);
+                const float v = mfma_epilogue<EPI>(acc[i][j][r]);
+                if (m < s.m && n < s.n) store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+            });
+        }
     });
 }
 
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int LOAD, int EPI, typename OutT>
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, LOAD, EPI, OutT>;
+    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;
     const int tm = (max_m + BM - 1) / BM, tn = (max_n + BN - 1) / BN;
     const int64_t tiles = (int64_t)tm * tn * plan.groups;
     const int64_t nblk = (tiles + 7) / 8 * 8;
@@ -373,24 +416,24 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }
 
-template <int BM, int BN, int WM, int WN, int LOAD, int EPI, typename OutT>
+template <int BM, int BN, int WM, int WN, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_layout(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    if (plan.a_kc && plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, true, LOAD, EPI, OutT>(plan, max_m, max_n, st);
-    if (plan.a_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, LOAD, EPI, OutT>(plan, max_m, max_n, st);
-    if (plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, false, true, LOAD, EPI, OutT>(plan, max_m, max_n, st);
-    return launch_mfma_cfg<BM, BN, WM, WN, false, false, LOAD, EPI, OutT>(plan, max_m, max_n, st);
+    if (plan.a_kc && plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, true, ODD, EPI, OutT>(plan, max_m, max_n, st);
+    if (plan.a_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
+    if (plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, false, true, ODD, EPI, OutT>(plan, max_m, max_n, st);
+    return launch_mfma_cfg<BM, BN, WM, WN, false, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
 }
 
 // fp32 results carry no epilogue on this path (GeLU of a P(sum) partial is rejected upstream and
 // fp32 inputs take the generic kernel), so three (epilogue, output) pairs cover every request.
-template <int BM, int BN, int WM, int WN, int LOAD>
+template <int BM, int BN, int WM, int WN, int ODD>
 int32_t launch_mfma_out(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
     if (plan.out_dtype == SBP_F32) {
         if (plan.epilogue != SBP_EPI_NONE) return SBP_ERR_UNSUPPORTED;
-        return launch_mfma_layout<BM, BN, WM, WN, LOAD, SBP_EPI_NONE, float>(plan, max_m, max_n, st);
+        return launch_mfma_layout<BM, BN, WM, WN, ODD, SBP_EPI_NONE, float>(plan, max_m, max_n, st);
     }
-    if (plan.epilogue == SBP_EPI_GELU) return launch_mfma_layout<BM, BN, WM, WN, LOAD, SBP_EPI_GELU, uint16_t>(plan, max_m, max_n, st);
-    return launch_mfma_layout<BM, BN, WM, WN, LOAD, SBP_EPI_NONE, uint16_t>(plan, max_m, max_n, st);
+    if (plan.epilogue == SBP_EPI_GELU) return launch_mfma_layout<BM, BN, WM, WN, ODD, SBP_EPI_GELU, uint16_t>(plan, max_m, max_n, st);
+    return launch_mfma_layout<BM, BN, WM, WN, ODD, SBP_EPI_NONE, uint16_t>(plan, max_m, max_n, st);
 }
 
 template <bool IN_BF16, typename OutT>
@@ -449,8 +492,6 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         case 2: return launch_mfma_out<256, 256, 2, 2, 0>(plan, max_m, max_n, stream);
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
         case 4: return launch_mfma_out<128, 128, 2, 2, 0>(plan, max_m, max_n, stream);
-        case 5: return launch_mfma_out<256, 256, 2, 2, 1>(plan, max_m, max_n, stream);
-        case 6: return launch_mfma_out<256, 256, 2, 4, 1>(plan, max_m, max_n, stream);
         default: return SBP_ERR_UNSUPPORTED;
     }
 }
