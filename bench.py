@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--cpu-rows", type=int, default=512, help="token rows in the oracle's sample")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="token rows in the oracle's sample")
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     return ap.parse_args()
 

@@ -6,7 +6,8 @@ import os
 from typing import Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libsbp_mi355x.so")
+# SBP_LIB names an alternative build of the same library (development / timing experiments)
+_LIB_PATH = os.environ.get("SBP_LIB") or os.path.join(HERE, "libsbp_mi355x.so")
 
 # signatures (sbp_t)
 def S(axis: int) -> int:

@@ -28,8 +28,7 @@ FLAGS = [
 ]
 
 
-def _compile(src: str, extra: list[str]) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra: list[str], obj: str) -> str:
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
@@ -41,16 +40,25 @@ def _compile(src: str, extra: list[str]) -> str:
     return obj
 
 
-def build(extra_flags: list[str] | None = None, verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(extra_flags: list[str] | None = None, verbose: bool = False, out: str | None = None) -> str:
+    """Compile every source and link.  `out` (with its own object folder) is for development builds."""
+    global OBJ
+    lib = out or LIB
+    obj_dir = OBJ if out is None else os.path.splitext(out)[0] + "_obj"
+    os.makedirs(obj_dir, exist_ok=True)
     extra = list(extra_flags or [])
+
+    def one(src):
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        return _compile(src, extra, obj)
+
     with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+        objs = list(ex.map(one, SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     subprocess.check_call(cmd)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":

@@ -9,6 +9,7 @@
 //
 // Operand storage: "KC" = reduction index contiguous ([m][kk] for A, [n][kk] for B), otherwise the
 // reduction index is the slow one ([kk][m], [kk][n]).  Row-major X and W give A KC and B not-KC.
+#include <cstdlib>
 #include <utility>
 
 #include "sbp_internal.h"
@@ -71,29 +72,43 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmPlan p) {
 // ------------------------------------------------------------------------------------------------
 // MFMA kernel
 // ------------------------------------------------------------------------------------------------
-constexpr int BK = 64;  // reduction extent of one LDS stage, in elements (128 B per KC row)
+// Timing experiments only: bit 0 no global loads, bit 1 no LDS reads in the loop, bit 2 no barrier,
+// bit 3 no scheduling hints.  A product build always has SBP_DBG == 0.
+#ifndef SBP_DBG
+#define SBP_DBG 0
+#endif
+
+constexpr int BK = 64;  // reduction extent of one LDS stage of gemm_mfma_kernel, in elements
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 typedef __attribute__((address_space(1))) const char gbl_char;
 
-// LDS image of a KC tile: row-major [R][64], the eight 16-byte chunks of a 128-byte row permuted by
-// XOR with swz(row).  8 consecutive rows use 8 different chunk slots and rows r, r + 8 differ too, so
-// the 16 rows a ds_read_b128 serves per pass cover all 64 banks (measured conflict-free on gfx950).
-__device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
-// LDS image of a not-KC tile: [64][R] with the 16-byte chunks of kk-row q permuted by XOR with
+// LDS image of a KC tile: row-major [R][BKT], the 16-byte chunks of a row permuted by XOR with
+// kswz(row).  A ds_read_b128 serves 16 lanes (16 consecutive rows, one chunk column) per pass and
+// the LDS has 64 banks of 4 bytes, so those 16 chunks must fall in 16 different 16-byte bank groups:
+//   BKT = 64 (128-byte rows): XOR with (row ^ row >> 3) & 7, BKT = 32 (64-byte rows): (row >> 2) & 3.
+// Both measured conflict-free on gfx950 (SQ_LDS_BANK_CONFLICT = 0).
+template <int BKT>
+__device__ inline int kswz(int row) {
+    if constexpr (BKT == 64) return (row ^ (row >> 3)) & 7;
+    else return (row >> 2) & 3;
+}
+// LDS image of a not-KC tile: [BKT][R] with the 16-byte chunks of kk-row q permuted by XOR with
 // nswz(q).  A ds_read_b64_tr_b16 serves 32 lanes per pass: 4 consecutive kk-rows x 64 contiguous
 // bytes.  Row pitch is a multiple of 256 B, so without the permutation the 4 rows share banks;
 // moving row q by (q % 4) * 64 B spreads them over all 64 banks.
 __device__ inline int nswz(int krow) { return (krow & 3) << 2; }
 
-template <int R, bool KC, int NT>
+template <int R, bool KC, int NT, int BKT = BK>
 struct Tile {
-    static constexpr int BYTES = R * BK * 2;
+    static constexpr int BYTES = R * BKT * 2;
     static constexpr int CHUNKS = BYTES / 16;
     static constexpr int PER_THREAD = CHUNKS / NT;
-    static constexpr int CPR = R / 8;   // 16-byte chunks per kk-row of a not-KC tile
+    static constexpr int CPR = R / 8;        // 16-byte chunks per kk-row of a not-KC tile
+    static constexpr int CPK = BKT / 8;      // 16-byte chunks per row of a KC tile
+    static constexpr int ROWB = BKT * 2;     // bytes per row of a KC tile
     static_assert(CHUNKS % NT == 0, "tile must divide over the workgroup");
     static_assert(KC || CPR >= 16, "not-KC swizzle needs at least 16 chunks per row");
 
@@ -102,10 +117,10 @@ struct Tile {
     // columns past the limit are clamped to valid memory and never reach an output.
     __device__ static uint32_t src_offset(int ld, int first, int limit, int p) {
         if constexpr (KC) {
-            const int row = p >> 3;
+            const int row = p / CPK;
             int g = first + row;
             g = g < limit ? g : limit - 1;
-            return ((uint32_t)g * (uint32_t)ld + (uint32_t)(((p & 7) ^ swz(row)) * 8)) * 2u;
+            return ((uint32_t)g * (uint32_t)ld + (uint32_t)(((p % CPK) ^ kswz<BKT>(row)) * 8)) * 2u;
         } else {
             const int krow = p / CPR;
             int col = first + (((p % CPR) ^ nswz(krow)) * 8);
@@ -113,8 +128,8 @@ struct Tile {
             return ((uint32_t)krow * (uint32_t)ld + (uint32_t)col) * 2u;
         }
     }
-    // bytes to advance the source by for one BK step
-    __device__ static uint32_t step_bytes(int ld) { return KC ? BK * 2u : (uint32_t)ld * BK * 2u; }
+    // bytes to advance the source by for one BKT step
+    __device__ static uint32_t step_bytes(int ld) { return KC ? BKT * 2u : (uint32_t)ld * BKT * 2u; }
 
     // global -> LDS without passing through registers: each lane's 16 bytes land at
     // lds + 16 * (p0 + lane), p0 uniform per wave instruction (wave must be a uniform value).
@@ -127,8 +142,6 @@ struct Tile {
         }
     }
 
-    // LDS -> one 32x32x16 MFMA operand for tile rows base .. base + 31 (base a multiple of 32):
-    // lane l gets the 8 values kk = 16 ks + 8 (l / 32) + 0..7 of row base + l % 32.
     // Fragment addressing.  The compiler tags an LDS access with the __shared__ object it touches
     // only through SHORT pointer chains, and it needs that tag to see that fragment reads of one
     // stage cannot alias direct-to-LDS loads into another (otherwise it serialises them with a
@@ -137,13 +150,13 @@ struct Tile {
     // immediate offset.  A KC tile needs one lane offset per ks (the swizzle XORs ks into the chunk
     // index), a not-KC tile one per 32-wide block (the swizzle XORs the block index).
     template <int F>
-    static constexpr int nlo() { return KC ? BK / 16 : F; }
+    static constexpr int nlo() { return KC ? BKT / 16 : F; }
 
     __device__ static int lane_offset(int idx, int wave_base, int lane) {
         int off;
-        if constexpr (KC) {   // idx = ks; block i adds i * 32 * 128
+        if constexpr (KC) {   // idx = ks; block i adds i * 32 * ROWB
             const int row = wave_base + (lane & 31);
-            off = row * 128 + (((2 * idx + (lane >> 5)) ^ swz(row)) << 4);
+            off = row * ROWB + (((2 * idx + (lane >> 5)) ^ kswz<BKT>(row)) << 4);
         } else {              // idx = block; ks adds 16 ks * R * 2, the second read 4 * R * 2
             const int s = lane & 15, nh = (lane >> 4) & 1, kh = lane >> 5;
             const int krow = 8 * kh + (s >> 2);
@@ -159,8 +172,10 @@ struct Tile {
     template <int NLO>
     __device__ static bf16x8 frag(const char* lds_tile, const int (&lo)[NLO], int blk, int ks) {
         if constexpr (KC) {
-            // swz(row + 32 blk) differs from swz(row) by (4 blk) & 7: odd blocks flip chunk bit 2
-            const int off = (lo[ks] ^ ((blk & 1) << 6)) + blk * 32 * 128;
+            // BKT = 64: kswz(row + 32 blk) differs from kswz(row) by (4 blk) & 7, i.e. odd blocks flip
+            // chunk bit 2.  BKT = 32: kswz does not depend on blk.
+            const int flip = BKT == 64 ? ((blk & 1) << 6) : 0;
+            const int off = (lo[ks] ^ flip) + blk * 32 * ROWB;
             return *reinterpret_cast<const bf16x8*>(lds_tile + off);
         } else {
             // ds_read_b64_tr_b16: in each group of 16 lanes, lane s supplies the address of 4
@@ -243,11 +258,41 @@ __device__ inline float mfma_epilogue(float v) {
     else return v;
 }
 
+// Epilogue of both MFMA kernels.  D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r].
+// Compile-time tile indices: the accumulators must never be indexed dynamically (they would move
+// to scratch memory).  Interior tiles (uniform test) store without per-element guards.
+template <int BM, int BN, int TM, int TN, int FM, int FN, int EPI, typename OutT>
+__device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&acc)[FM][FN], const GemmShard& s, int m0, int n0, int wm, int wn, int lane) {
+    OutT* C = static_cast<OutT*>(s.c);
+    const int cn = lane & 31, rm = 4 * (lane >> 5);
+    const bool whole = m0 + BM <= s.m && n0 + BN <= s.n;
+    static_for<FM * FN>([&](auto idx) {
+        constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
+        const int n = n0 + wn * TN + j * 32 + cn;
+        const int mb = m0 + wm * TM + i * 32 + rm;
+        OutT* cp = C + (int64_t)mb * s.ldc + n;
+        if (whole) {
+            static_for<16>([&](auto ridx) {
+                constexpr int r = decltype(ridx)::value;
+                store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, mfma_epilogue<EPI>(acc[i][j][r]));
+            });
+        } else {
+            static_for<16>([&](auto ridx) {
+                constexpr int r = decltype(ridx)::value;
+                const int m = mb + 8 * (r >> 2) + (r & 3);
+                const float v = mfma_epilogue<EPI>(acc[i][j][r]);
+                if (m < s.m && n < s.n) store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+            });
+        }
+    });
+}
+
 // Scheduling hint for one phase of NMFMA matrix instructions: let one LDS read and (for the first NVM
 // of them) one global->LDS load issue behind each MFMA, so that the operands of the NEXT phase stream
 // in underneath the matrix pipe instead of in a burst right before they are needed.
 template <int NMFMA, int NDS, int NVM>
 __device__ inline void pace() {
+    if constexpr (SBP_DBG & 8) return;
     static_for<NMFMA>([&](auto i) {
         constexpr int I = decltype(i)::value;
         constexpr int nds = NDS * (I + 1) / NMFMA - NDS * I / NMFMA;   // spread evenly, all before the phase ends
@@ -316,6 +361,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
     for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
 
     auto read_frags = [&](const char* sa, const char* sb, int ks, int slot) {
+        if constexpr (SBP_DBG & 2) {
+            if (ks != 100) return;   // experiment: only the priming read (ks == 100) touches LDS
+            ks = 0;
+        }
 #pragma unroll
         for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, lob, j, ks);
 #pragma unroll
@@ -340,8 +389,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
         const char* sb = CUR ? sB1 : sB0;
         char* da = CUR ? sA0 : sA1;
         char* db = CUR ? sB0 : sB1;
-        TA::load_direct(da, A, offa, wave);
-        TB::load_direct(db, B, offb, wave);
+        if constexpr (!(SBP_DBG & 1)) {
+            TA::load_direct(da, A, offa, wave);
+            TB::load_direct(db, B, offb, wave);
+        }
         ++t;
         const bool adv = t + 1 < steps;      // tile t + 1 exists (t already counts this step)
         A += adv ? stepa : 0u;
@@ -355,8 +406,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
         read_frags(sa, sb, 3, 1);
         mfmas(0);
         pace<FM * FN, NDS, 0>();
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's direct-to-LDS loads have landed
-        __syncthreads();
+        if constexpr (!(SBP_DBG & 4)) {
+            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): loads landed, fragment reads returned
+            __builtin_amdgcn_s_barrier();
+        }
         read_frags(da, db, 0, 0);
         mfmas(1);
         pace<FM * FN, NDS, 0>();
@@ -366,62 +419,193 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
 
     TA::load_direct(sA0, A, offa, wave);
     TB::load_direct(sB0, B, offb, wave);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_waitcnt(0x0070);
     if (steps > 1) {
         A += stepa;
         B += stepb;
     }
-    __syncthreads();
-    read_frags(sA0, sB0, 0, 0);
+    __builtin_amdgcn_s_barrier();
+    read_frags(sA0, sB0, (SBP_DBG & 2) ? 100 : 0, 0);
+    if constexpr (SBP_DBG & 2) read_frags(sA0, sB0, 100, 1);
     for (int pair = 0; pair < steps / 2; ++pair) {
         step(I0{});
         step(I1{});
     }
     if (steps & 1) step(I0{});
 
-    // D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r].  Compile-time tile indices: the
-    // accumulators must never be indexed dynamically (they would move to scratch memory).
-    OutT* C = static_cast<OutT*>(s.c);
-    const int cn = lane & 31, rm = 4 * (lane >> 5);
-    const bool whole = m0 + BM <= s.m && n0 + BN <= s.n;   // uniform: interior tiles store unguarded
-    static_for<FM * FN>([&](auto idx) {
-        constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
-        const int n = n0 + wn * TN + j * 32 + cn;
-        const int mb = m0 + wm * TM + i * 32 + rm;
-        OutT* cp = C + (int64_t)mb * s.ldc + n;
-        if (whole) {
-            static_for<16>([&](auto ridx) {
-                constexpr int r = decltype(ridx)::value;
-                store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, mfma_epilogue<EPI>(acc[i][j][r]));
-            });
-        } else {
-            static_for<16>([&](auto ridx) {
-                constexpr int r = decltype(ridx)::value;
-                const int m = mb + 8 * (r >> 2) + (r & 3);
-                const float v = mfma_epilogue<EPI>(acc[i][j][r]);
-                if (m < s.m && n < s.n) store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
-            });
-        }
+    store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Deeper pipeline: NST LDS stages of 32 reduction elements each (same 128 KB as 2 x 64 when
+// NST = 4), so that NST - 1 tiles are in flight while one is being multiplied.  One step t:
+//   issue the loads of tile t + NST - 1 into the stage that step t - 1 just finished with
+//   read the fragments of (t, ks = 1), run the MFMAs of (t, ks = 0)
+//   wait until only the loads of tiles t + 2 .. are outstanding (they complete in order), barrier
+//   read the fragments of (t + 1, ks = 0), run the MFMAs of (t, ks = 1)
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int NST, int EPI, typename OutT>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_pipe_kernel(GemmPlan p, int tm, int tn) {
+    constexpr int BKT = 32;
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int FM = TM / 32, FN = TN / 32;
+    constexpr int NDS = (A_KC ? FM : 2 * FM) + (B_KC ? FN : 2 * FN);
+    using TA = Tile<BM, A_KC, NT, BKT>;
+    using TB = Tile<BN, B_KC, NT, BKT>;
+    constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
+    static_assert(NST >= 3 && NST <= 5, "3 to 5 stages");
+    static_assert((NST - 2) * NVM < 64, "vmcnt field");
+    __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA2[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA3[NST > 3 ? TA::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sA4[NST > 4 ? TA::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB2[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB3[NST > 3 ? TB::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sB4[NST > 4 ? TB::BYTES : 16];
+    auto stA = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sA0; else if constexpr (I == 1) return sA1; else if constexpr (I == 2) return sA2;
+        else if constexpr (I == 3) return sA3; else return sA4;
+    };
+    auto stB = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sB0; else if constexpr (I == 1) return sB1; else if constexpr (I == 2) return sB2;
+        else if constexpr (I == 3) return sB3; else return sB4;
+    };
+
+    const TileCoord tc = map_tile(blockIdx.x, gridDim.x, tm, tn, p.groups);
+    if (!tc.valid) return;
+    const GemmShard s = p.s[tc.g];
+    const int m0 = tc.tile_m * BM, n0 = tc.tile_n * BN;
+    if (m0 >= s.m || n0 >= s.n) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    gbl_char* A = (gbl_char*)s.a;
+    gbl_char* B = (gbl_char*)s.b;
+
+    uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+#pragma unroll
+    for (int it = 0; it < TA::PER_THREAD; ++it) offa[it] = TA::src_offset(s.lda, m0, s.m, it * NT + tid);
+#pragma unroll
+    for (int it = 0; it < TB::PER_THREAD; ++it) offb[it] = TB::src_offset(s.ldb, n0, s.n, it * NT + tid);
+    const uint32_t stepa = TA::step_bytes(s.lda), stepb = TB::step_bytes(s.ldb);
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 fa[2][FM], fb[2][FN];
+    int loa[TA::template nlo<FM>()], lob[TB::template nlo<FN>()];
+#pragma unroll
+    for (int x = 0; x < TA::template nlo<FM>(); ++x) loa[x] = TA::lane_offset(x, wm * TM, lane);
+#pragma unroll
+    for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
+
+    auto read_frags = [&](const char* sa, const char* sb, int ks, int slot) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, lob, j, ks);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[slot][i] = TA::frag(sa, loa, i, ks);
+    };
+    auto mfmas = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+    };
+
+    const int steps = s.kk / BKT;
+    int loaded = 0;   // tiles whose loads have been issued; the source pointers sit on tile min(loaded, steps - 1)
+    auto issue = [&](char* da, char* db) {
+        TA::load_direct(da, A, offa, wave);
+        TB::load_direct(db, B, offb, wave);
+        ++loaded;
+        const bool adv = loaded < steps;   // past the last tile the pointer stays: reloads are in bounds, unread
+        A += adv ? stepa : 0u;
+        B += adv ? stepb : 0u;
+    };
+    // s_waitcnt immediate: vmcnt(n), n < 64, split over bits 3:0 and 15:14; expcnt left at "no wait"
+    constexpr int WAIT_KEEP = (NST - 2) * NVM;
+    constexpr int WAIT_IMM = (WAIT_KEEP & 15) | ((WAIT_KEEP >> 4) << 14) | 0x0070;   // ... and lgkmcnt(0)
+
+    auto step = [&](auto cur) {
+        constexpr int CUR = decltype(cur)::value;
+        using Nxt = std::integral_constant<int, (CUR + 1) % NST>;
+        using Dst = std::integral_constant<int, (CUR + NST - 1) % NST>;
+        issue(stA(Dst{}), stB(Dst{}));
+        read_frags(stA(cur), stB(cur), 1, 1);
+        mfmas(0);
+        pace<FM * FN, NDS, NVM>();
+        // This wave's part of the next tile has landed (later tiles may still fly) and its own
+        // fragment reads have returned; then a bare hardware barrier.  __syncthreads() is not used:
+        // its workgroup fence counts direct-to-LDS loads as LDS stores and would drain ALL of them.
+        __builtin_amdgcn_s_waitcnt(WAIT_IMM);
+        __builtin_amdgcn_s_barrier();
+        read_frags(stA(Nxt{}), stB(Nxt{}), 0, 0);
+        mfmas(1);
+        pace<FM * FN, NDS, 0>();
+    };
+
+    static_for<NST - 1>([&](auto i) { issue(stA(i), stB(i)); });
+    __builtin_amdgcn_s_waitcnt(WAIT_IMM);
+    __builtin_amdgcn_s_barrier();
+    read_frags(sA0, sB0, 0, 0);
+    int t = 0;
+    for (; t + NST <= steps; t += NST) static_for<NST>([&](auto i) { step(i); });
+    const int rem = steps - t;   // 0 .. NST - 1 steps left, stage numbering continues from 0
+    static_for<NST - 1>([&](auto i) {
+        if (decltype(i)::value < rem) step(i);
     });
+    __builtin_amdgcn_s_waitcnt(0x0070);   // drain the (unread) trailing loads before LDS is released
+
+    store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
 }
 
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;
+    void (*kern)(GemmPlan, int, int);
+    if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
+    else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
     const int tm = (max_m + BM - 1) / BM, tn = (max_n + BN - 1) / BN;
     const int64_t tiles = (int64_t)tm * tn * plan.groups;
     const int64_t nblk = (tiles + 7) / 8 * 8;
     if (nblk > 0x7FFFFFFF) return SBP_ERR_UNSUPPORTED;
+#ifdef SBP_EXPERIMENT
+    // Timing experiment only (never in a product build): every operand row aliases row 0, so all
+    // loads stay in bounds and hit in cache.  Results are meaningless.
+    if (getenv("SBP_DEBUG_LD0")) {
+        GemmPlan q = plan;
+        for (int g = 0; g < q.groups; ++g) { q.s[g].lda = 0; q.s[g].ldb = 0; }
+        hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, q, tm, tn);
+        return SBP_OK;
+    }
+#endif
     hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn);
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }
 
 template <int BM, int BN, int WM, int WN, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_layout(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
+#ifdef SBP_EXPERIMENT_MIN
+    if (plan.a_kc && !plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
+    return SBP_ERR_UNSUPPORTED;
+#else
     if (plan.a_kc && plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, true, ODD, EPI, OutT>(plan, max_m, max_n, st);
     if (plan.a_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
     if (plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, false, true, ODD, EPI, OutT>(plan, max_m, max_n, st);
     return launch_mfma_cfg<BM, BN, WM, WN, false, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
+#endif
 }
 
 // fp32 results carry no epilogue on this path (GeLU of a P(sum) partial is rejected upstream and
@@ -487,11 +671,20 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         }
         return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
     }
+    if (variant == 0) {
+        // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages; shapes that would leave
+        // most of such a tile empty take the 128 x 128 tile.
+        variant = (max_m > 128 && max_n > 128) ? 6 : 4;
+    }
     switch (variant) {
-        case 0:
         case 2: return launch_mfma_out<256, 256, 2, 2, 0>(plan, max_m, max_n, stream);
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
+#ifndef SBP_EXPERIMENT_MIN
         case 4: return launch_mfma_out<128, 128, 2, 2, 0>(plan, max_m, max_n, stream);
+#endif
+        case 5: return launch_mfma_out<256, 256, 2, 2, 4>(plan, max_m, max_n, stream);
+        case 6: return launch_mfma_out<256, 256, 2, 4, 4>(plan, max_m, max_n, stream);
+        case 8: return launch_mfma_out<256, 256, 2, 4, 3>(plan, max_m, max_n, stream);
         default: return SBP_ERR_UNSUPPORTED;
     }
 }

@@ -148,10 +148,11 @@ def test_matmul_fp32_every_table1_row(k, sx, sw):
 
 @pytest.mark.parametrize("tx,tw", [(0, 0), (1, 0), (0, 1), (1, 1)])
 @pytest.mark.parametrize("sx,sw", [(orc.S0, orc.B), (orc.B, orc.S1), (orc.S1, orc.S0), (orc.B, orc.B)])
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 8])
 def test_matmul_bf16_mfma_shapes(sx, sw, tx, tw, variant):
     """several 256-tiles plus ragged M / N tails; K a multiple of 64 per shard.  variant 1 is the
-    generic kernel on the same data (both must agree with the oracle)."""
+    generic kernel on the same data, the others are MFMA kernel variants (tile split over 4 or 8
+    waves, 2 x 64 or 3-4 x 32 LDS stages); all must agree with the oracle."""
     k = 2
     M, K, N = 2 * 296, 2 * 192, 2 * 328        # per-shard 296 / 192 / 328 when split
     X, W = rnd_bf16(1, (M, K)), rnd_bf16(2, (K, N), 0.05)
