@@ -1,0 +1,256 @@
+"""GPU parity at the FULL sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot recompute whole outputs at these sizes in seconds, so each test checks
+  (a) sampled outputs the oracle computes one by one (rows chosen to hit every output tile), to the
+      same bars as the small tests, and
+  (b) properties that hold at any size, evaluated over the whole output on the device with plain
+      torch ops (used as plumbing): all B copies bit-identical, reductions equal to the fp32
+      shard-order sum of the partials the GPU itself produced, relayouts equal to slices of the
+      uploaded global tensor.
+Inputs come from the seeded generator only; nothing the HIP path produced is fed to the oracle.
+"""
+import numpy as np
+import pytest
+
+import oracle as orc
+import paper_2110_15032_amd as sbp
+import workloads as wl
+from sbp_harness import assert_bits_equal, assert_matmul_close, assert_psum_close, sync, torch_mod
+from workloads import CONFIGS
+
+pytestmark = pytest.mark.gpu
+SEED = wl.SEED_BASE
+
+
+def bf16_window(spec, rows=None, cols=None):
+    x = wl.normal(SEED, spec["id"], spec["shape"], spec["dist"][1], rows, cols, dtype=np.float32)
+    return wl.to_bf16_bits(x)
+
+
+def dev_u16(a):
+    torch = torch_mod()
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+
+
+def host_u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def tile_rows(n, tile, per_tile, seed):
+    """a few row indices inside every tile of `tile` rows (first, last and random ones)"""
+    rng = np.random.default_rng(seed)
+    out = []
+    for t0 in range(0, n, tile):
+        hi = min(t0 + tile, n)
+        pick = {t0, hi - 1} | set(int(x) for x in rng.integers(t0, hi, size=max(0, per_tile - 2)))
+        out.extend(sorted(pick))
+    return np.array(sorted(set(out)))
+
+
+# ----------------------------------------------------------------------------------------------
+def test_config2_mlp_block_full_size():
+    torch = torch_mod()
+    cfg = CONFIGS["mlp"]
+    k = cfg["k"]
+    T, D = cfg["X"]["shape"]
+    F = cfg["W1"]["shape"][1]
+    x = dev_u16(bf16_window(cfg["X"]))
+    x_sh = [x] + [x.clone() for _ in range(k - 1)]
+    w1_sh = [dev_u16(bf16_window(cfg["W1"], cols=np.arange(*wl.split_range(F, k, i)))) for i in range(k)]
+    w2_sh = [dev_u16(bf16_window(cfg["W2"], rows=np.arange(*wl.split_range(F, k, i)))) for i in range(k)]
+    h_sh = [torch.full((T, F // k), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    y_sh = [torch.full((T, D), float("nan"), device="cuda") for _ in range(k)]
+    yb_sh = [torch.full((T, D), float("nan"), device="cuda") for _ in range(k)]
+    X, W1, W2 = sbp.SbpTensor(x_sh, T, D, sbp.BF16), sbp.SbpTensor(w1_sh, D, F, sbp.BF16), sbp.SbpTensor(w2_sh, F, D, sbp.BF16)
+    H, Y, Yb = sbp.SbpTensor(h_sh, T, F, sbp.BF16), sbp.SbpTensor(y_sh, T, D, sbp.F32), sbp.SbpTensor(yb_sh, T, D, sbp.F32)
+    sbp.sbp_matmul_ex(X, sbp.B, W1, sbp.S(1), H, sbp.S(1), k, None, sbp.EPI_GELU)
+    sbp.sbp_matmul(H, sbp.S(1), W2, sbp.S(0), Y, sbp.P_SUM, k)
+    sbp.sbp_boxing(Y, sbp.P_SUM, Yb, sbp.B, k)
+    sync()
+
+    # (b) whole-output properties
+    acc = y_sh[0].clone()
+    for i in range(1, k):
+        acc += y_sh[i]                       # fp32, shard order: what the library documents
+    for j in range(k):
+        assert torch.equal(yb_sh[j], acc), f"P->B copy {j} is not the fp32 shard-order sum of the partials"
+    assert not torch.isnan(acc).any()
+
+    # (a) sampled token rows through the oracle, every 256-row tile hit
+    rows = tile_rows(T, 256, 3, 7)
+    Xr = orc.bf16_to_f64(bf16_window(cfg["X"], rows=rows))
+    W1h = [orc.bf16_to_f64(host_u16(w)) for w in w1_sh]     # the uploaded words themselves (generator output)
+    W2h = [orc.bf16_to_f64(host_u16(w)) for w in w2_sh]
+    Hs, s_h = orc.matmul_sbp([Xr] * k, orc.B, W1h, orc.S1)
+    assert s_h == orc.S1
+    Hq = [orc.bf16_round(orc.gelu(h)) for h in Hs]
+    Ys, s_y = orc.matmul_sbp([orc.bf16_to_f64(h) for h in Hq], orc.S1, W2h, orc.S0)
+    assert s_y == orc.P_SUM
+    Yref = orc.assemble(Ys, orc.P_SUM)
+    ridx = torch.from_numpy(rows).cuda()
+    worst = 0.0
+    for i in range(k):
+        got_h = orc.bf16_to_f64(host_u16(h_sh[i][ridx]))
+        assert_matmul_close(got_h, orc.bf16_to_f64(Hq[i]), 2e-2, f"H shard {i}")
+        got_y = y_sh[i][ridx].cpu().numpy()
+        worst = max(worst, assert_matmul_close(got_y, Ys[i], 2e-2, f"Y partial {i}"))
+    got = yb_sh[0][ridx].cpu().numpy()
+    assert_matmul_close(got, Yref, 2e-2, "Y after P->B")
+    parts_gpu = [y_sh[i][ridx].cpu().numpy() for i in range(k)]
+    assert_psum_close(got, parts_gpu, orc.assemble(parts_gpu, orc.P_SUM), "P->B against the oracle's sum of the same partials")
+    print(f"config 2: worst relative error of the fp32 partials {worst:.2e}")
+
+
+# ----------------------------------------------------------------------------------------------
+def test_config3_dp_weight_gradient_full_size():
+    torch = torch_mod()
+    cfg = CONFIGS["dp_grad"]
+    k = cfg["k"]
+    Tk, Din = cfg["X"]["shape"]       # 16384 tokens, 1024
+    Dout = cfg["dY"]["shape"][1]      # 4096
+    Xw, dYw = bf16_window(cfg["X"]), bf16_window(cfg["dY"])
+    # X is S(0) by tokens; the operand of dW = X^T dY is X^T [1024, 16384], split S(1), stored transposed
+    x_sh = [dev_u16(Xw[slice(*wl.split_range(Tk, k, i))]) for i in range(k)]
+    dy_sh = [dev_u16(dYw[slice(*wl.split_range(Tk, k, i))]) for i in range(k)]
+    dw_sh = [torch.full((Din, Dout), float("nan"), device="cuda") for _ in range(k)]
+    dws_sh = [torch.full((Din // k, Dout), float("nan"), device="cuda") for _ in range(k)]
+    dwb_sh = [torch.full((Din, Dout), float("nan"), device="cuda") for _ in range(k)]
+    XT = sbp.SbpTensor(x_sh, Din, Tk, sbp.BF16, trans=1)
+    DY = sbp.SbpTensor(dy_sh, Tk, Dout, sbp.BF16)
+    DW = sbp.SbpTensor(dw_sh, Din, Dout, sbp.F32)
+    DWS = sbp.SbpTensor(dws_sh, Din, Dout, sbp.F32)
+    DWB = sbp.SbpTensor(dwb_sh, Din, Dout, sbp.F32)
+    sbp.sbp_matmul(XT, sbp.S(1), DY, sbp.S(0), DW, sbp.P_SUM, k)
+    sbp.sbp_boxing(DW, sbp.P_SUM, DWS, sbp.S(0), k)
+    sbp.sbp_boxing(DW, sbp.P_SUM, DWB, sbp.B, k)
+    sync()
+    # the oracle does this one in full: 8 local products X_i^T dY_i in float64
+    Xs = [orc.bf16_to_f64(Xw[slice(*wl.split_range(Tk, k, i))]).T.copy() for i in range(k)]
+    dYs = [orc.bf16_to_f64(dYw[slice(*wl.split_range(Tk, k, i))]) for i in range(k)]
+    parts, sy = orc.matmul_sbp(Xs, orc.S1, dYs, orc.S0)
+    assert sy == orc.P_SUM
+    got_parts = [t.cpu().numpy() for t in dw_sh]
+    for i in range(k):
+        assert_matmul_close(got_parts[i], parts[i], 2e-2, f"dW partial {i}")
+        assert_matmul_close(got_parts[i], parts[i], 1e-4, f"dW partial {i} (fp32 accumulation of exact products)")
+    ref_gpu_sum = orc.assemble(got_parts, orc.P_SUM)          # float64 sum of the GPU's partials
+    for j, t in enumerate(dwb_sh):
+        assert_psum_close(t.cpu().numpy(), got_parts, ref_gpu_sum, f"P->B copy {j}")
+        assert torch.equal(t, dwb_sh[0])
+    ref_s = orc.boxing(got_parts, orc.P_SUM, orc.S0, k)
+    for j, t in enumerate(dws_sh):
+        sl = slice(*orc.split_range(Din, k, j))
+        assert_psum_close(t.cpu().numpy(), [p[sl] for p in got_parts], ref_s[j], f"P->S(0) shard {j}")
+        assert torch.equal(t, dwb_sh[0][sl]), "reduce-scatter slice differs from the all-reduce result"
+    assert_matmul_close(dwb_sh[0].cpu().numpy(), orc.assemble(parts, orc.P_SUM), 2e-2, "dW")
+
+
+# ----------------------------------------------------------------------------------------------
+def test_config4_classifier_head_full_size():
+    torch = torch_mod()
+    cfg = CONFIGS["classifier"]
+    k = cfg["k"]
+    R, Dm = cfg["F"]["shape"]         # 1024, 512
+    C = cfg["W"]["shape"][1]          # 1,000,000 classes
+    Fw = bf16_window(cfg["F"])
+    f = dev_u16(Fw)
+    f_sh = [f] + [f.clone() for _ in range(k - 1)]
+    w_host = [bf16_window(cfg["W"], cols=np.arange(*wl.split_range(C, k, i))) for i in range(k)]   # [512, 125000] each
+    w_sh = [dev_u16(w) for w in w_host]
+    Ci = C // k
+    l_sh = [torch.full((R, Ci), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    vec = lambda: [torch.full((R, 1), float("nan"), device="cuda") for _ in range(k)]      # noqa: E731
+    mp, mb, sp, sb = vec(), vec(), vec(), vec()
+    Ft, Wt = sbp.SbpTensor(f_sh, R, Dm, sbp.BF16), sbp.SbpTensor(w_sh, Dm, C, sbp.BF16)
+    L = sbp.SbpTensor(l_sh, R, C, sbp.BF16)
+    MP, MB, SP, SB = (sbp.SbpTensor(v, R, 1, sbp.F32) for v in (mp, mb, sp, sb))
+    sbp.sbp_matmul(Ft, sbp.B, Wt, sbp.S(1), L, sbp.S(1), k)
+    sbp.sbp_row_max(L, sbp.S(1), MP, k)
+    sbp.sbp_boxing(MP, sbp.P_MAX, MB, sbp.B, k)
+    sbp.sbp_row_sumexp(L, sbp.S(1), MB, SP, k)
+    sbp.sbp_boxing(SP, sbp.P_SUM, SB, sbp.B, k)
+    sync()
+
+    # (b) whole-output properties on the device
+    lf = [t.view(torch.bfloat16).float() for t in l_sh]
+    for i in range(k):
+        assert torch.equal(mp[i][:, 0], lf[i].max(dim=1).values), f"local row max {i}"
+    gmax = torch.stack([m[:, 0] for m in mp]).max(dim=0).values
+    for j in range(k):
+        assert torch.equal(mb[j][:, 0], gmax), "global max copy"
+        ref_s = torch.exp(lf[j].double() - gmax.double()[:, None]).sum(dim=1)
+        assert torch.allclose(sp[j][:, 0].double(), ref_s, rtol=2e-5, atol=0), f"local sum-exp {j}"
+    tot = sp[0].clone()
+    for i in range(1, k):
+        tot += sp[i]
+    for j in range(k):
+        assert torch.equal(sb[j], tot), "denominator copy"
+    del lf
+
+    # (a) sampled feature rows through the oracle (all 10^6 classes of each), shard by shard
+    rows = tile_rows(R, 256, 3, 11)
+    Fr = orc.bf16_to_f64(Fw[rows])
+    ridx = torch.from_numpy(rows).cuda()
+    m_loc, logits_q = [], []
+    for i in range(k):
+        ref = orc.matmul(Fr, orc.bf16_to_f64(w_host[i]))
+        got = orc.bf16_to_f64(host_u16(l_sh[i][ridx]))
+        assert_matmul_close(got, ref, 2e-2, f"logits shard {i}")
+        q = orc.bf16_to_f64(orc.bf16_round(ref))
+        logits_q.append(q)
+        m_loc.append(orc.row_max(q)[:, None])
+    m = orc.boxing(m_loc, orc.P_MAX, orc.B, k)[0][:, 0]
+    got_m = mb[0][ridx, 0].cpu().numpy().astype(np.float64)
+    # the two sides round the same accumulations to bf16 independently: at most one bf16 step apart
+    assert np.all(np.abs(got_m - m) <= 2.0 ** -7 * np.abs(m)), "global max vs oracle"
+    s_loc = [orc.row_sumexp(q, m)[:, None] for q in logits_q]
+    s = orc.boxing(s_loc, orc.P_SUM, orc.B, k)[0][:, 0]
+    got_s = sb[0][ridx, 0].cpu().numpy().astype(np.float64)
+    # softmax denominator: s * exp(m) is what does not depend on which of two adjacent bf16 values the max took
+    assert np.allclose(np.log(got_s) + got_m, np.log(s) + m, rtol=0, atol=2e-2), "softmax denominator vs oracle"
+
+
+# ----------------------------------------------------------------------------------------------
+def test_config5_relayout_full_size():
+    torch = torch_mod()
+    cfg = CONFIGS["relayout"]
+    k = cfg["k"]
+    R, C = cfg["T"]["shape"]          # 65536 x 8192 16-bit words
+    Rk, Ck = R // k, C // k
+    s0 = [dev_u16(wl.pattern_u16((R, C), rows=np.arange(i * Rk, (i + 1) * Rk))) for i in range(k)]
+    G = torch.cat(s0, dim=0)          # the global tensor, for whole-output checks by slicing
+    s1 = [torch.full((R, Ck), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    T0, T1 = sbp.SbpTensor(s0, R, C, sbp.BF16), sbp.SbpTensor(s1, R, C, sbp.BF16)
+    sbp.sbp_boxing(T0, sbp.S(0), T1, sbp.S(1), k)            # all2all
+    sync()
+    for j in range(k):
+        assert torch.equal(s1[j], G[:, j * Ck:(j + 1) * Ck]), f"S(0)->S(1) shard {j}"
+    # sampled rows through the oracle (a row subset of an S(0)->S(1) conversion is the same conversion)
+    rows = tile_rows(R, 4096, 3, 5)
+    sub = wl.pattern_u16((R, C), rows=rows)
+    ref = orc.boxing(orc.scatter(sub, orc.S1, k), orc.S1, orc.S1, k)
+    ridx = torch.from_numpy(rows).cuda()
+    for j in range(k):
+        assert_bits_equal(host_u16(s1[j][ridx]), ref[j], f"S(0)->S(1) sampled rows, shard {j}")
+    del s0
+
+    b = [torch.full((R, C), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]     # 16 x 1 GiB
+    TB = sbp.SbpTensor(b, R, C, sbp.BF16)
+    sbp.sbp_boxing(T1, sbp.S(1), TB, sbp.B, k)               # all-gather
+    sync()
+    for j in range(k):
+        assert torch.equal(b[j], G), f"S(1)->B copy {j}"
+    refB = orc.boxing(orc.scatter(sub, orc.S1, k), orc.S1, orc.B, k)
+    assert_bits_equal(host_u16(b[k - 1][ridx]), refB[k - 1], "S(1)->B sampled rows")
+    del s1, T1
+
+    # B -> S(0) reads device j's OWN copy: make the copies differ in one word each to see that
+    for j in range(k):
+        b[j][j * Rk, 0] = j + 1
+    out = [torch.full((Rk, C), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    TO = sbp.SbpTensor(out, R, C, sbp.BF16)
+    sbp.sbp_boxing(TB, sbp.B, TO, sbp.S(0), k)               # local slice
+    sync()
+    for j in range(k):
+        assert torch.equal(out[j], b[j][j * Rk:(j + 1) * Rk]), f"B->S(0) shard {j}"
+        assert int(out[j][0, 0]) == j + 1
