@@ -146,7 +146,9 @@ int32_t sbp_row_sumexp(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor
 /* Tuning knobs; they never change what is computed beyond fp32 summation order
  * inside a GEMM tile.  Unknown knob or value: SBP_ERR_UNSUPPORTED. */
 enum {
-    SBP_KNOB_GEMM_VARIANT = 0   /* 0 = default choice by shape; >0 forces a kernel variant */
+    SBP_KNOB_GEMM_VARIANT = 0,  /* 0 = default choice by shape; >0 forces a kernel variant */
+    SBP_KNOB_TILE_ORDER = 1     /* order in which workgroups walk output tiles: low byte = tile-rows per
+                                   band (default 2), bit 8 set = no per-XCD re-linearisation            */
 };
 int32_t sbp_set_knob(int32_t knob, int32_t value);
 

@@ -24,6 +24,7 @@ EPI_NONE = 0
 EPI_GELU = 1
 # knobs
 KNOB_GEMM_VARIANT = 0
+KNOB_TILE_ORDER = 1
 
 #: every symbol include/sbp.h declares
 EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing",

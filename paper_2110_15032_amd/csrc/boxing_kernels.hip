@@ -15,6 +15,8 @@
 //
 // HBM-bound: every input byte is read once and every output byte written once, with the widest
 // vector (up to 16 B per lane) that all offsets and pitches of the conversion allow.
+#include <cstdlib>
+
 #include "sbp_internal.h"
 
 namespace sbp {
@@ -223,10 +225,19 @@ void launch_reduce_k(const BoxParams& p, dim3 grid, hipStream_t st) {
 }
 
 template <int OP>
-void launch_reduce(const BoxParams& p, dim3 grid, hipStream_t st) {
-    if (p.vec_elems == 4) launch_reduce_k<f32x4, OP, 2>(p, grid, st);
-    else if (p.vec_elems == 2) launch_reduce_k<f32x2, OP, 2>(p, grid, st);
-    else launch_reduce_k<float, OP, 2>(p, grid, st);
+void launch_reduce(const BoxParams& p, dim3 grid, int unroll, hipStream_t st) {
+    if (p.vec_elems == 4) {
+        if (unroll == 2) launch_reduce_k<f32x4, OP, 2>(p, grid, st);
+        else launch_reduce_k<f32x4, OP, 1>(p, grid, st);
+    } else if (p.vec_elems == 2) launch_reduce_k<f32x2, OP, 1>(p, grid, st);
+    else launch_reduce_k<float, OP, 1>(p, grid, st);
+}
+
+template <typename V>
+void launch_copy(const BoxParams& p, dim3 grid, int unroll, hipStream_t st) {
+    if (unroll == 1) hipLaunchKernelGGL((box_copy_kernel<V, 1>), grid, dim3(BOX_THREADS), 0, st, p);
+    else if (unroll == 2) hipLaunchKernelGGL((box_copy_kernel<V, 2>), grid, dim3(BOX_THREADS), 0, st, p);
+    else hipLaunchKernelGGL((box_copy_kernel<V, 4>), grid, dim3(BOX_THREADS), 0, st, p);
 }
 
 }  // namespace
@@ -291,22 +302,31 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     if (max_units >= (int64_t)1 << 31) return SBP_ERR_UNSUPPORTED;
 
     const bool reduce = p_in && plan.sbp_in != plan.sbp_out;
-    const int unroll = reduce ? 2 : 4;
+    // Streaming kernels run fastest on this chip as many short-lived workgroups: one vector per lane
+    // and a grid that covers the data in one pass up to a cap.  Measured on the 8-way all-reduce of
+    // 1 GiB: 5.99 TB/s this way against 5.1-5.4 TB/s for a 2048-block grid-stride loop; on the
+    // 1 GiB all2all 6.4 TB/s against 5.3 TB/s.
+    int unroll = 1;
+    int64_t cap_total = reduce ? 65536 : 131072;
+#ifdef SBP_EXPERIMENT
+    if (const char* e = getenv("SBP_BOX_UNROLL")) unroll = atoi(e);
+    if (const char* e = getenv("SBP_BOX_CAP")) cap_total = atoll(e);
+#endif
     int64_t bx = (max_units + (int64_t)BOX_THREADS * unroll - 1) / ((int64_t)BOX_THREADS * unroll);
-    const int64_t cap = (8192 + tasks - 1) / tasks;  // about 32 blocks per CU over the whole launch
+    const int64_t cap = (cap_total + tasks - 1) / tasks;
     if (bx > cap) bx = cap;
     if (bx < 1) bx = 1;
     const dim3 grid((uint32_t)bx, (uint32_t)tasks);
 
     if (reduce) {
-        if (plan.sbp_in == SBP_P_SUM) launch_reduce<BOX_SUM>(p, grid, stream);
-        else launch_reduce<BOX_MAX>(p, grid, stream);
+        if (plan.sbp_in == SBP_P_SUM) launch_reduce<BOX_SUM>(p, grid, unroll, stream);
+        else launch_reduce<BOX_MAX>(p, grid, unroll, stream);
     } else {
         const int vb = p.vec_elems * plan.elem_bytes;
-        if (vb == 16) hipLaunchKernelGGL((box_copy_kernel<u32x4, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
-        else if (vb == 8) hipLaunchKernelGGL((box_copy_kernel<u32x2, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
-        else if (vb == 4) hipLaunchKernelGGL((box_copy_kernel<uint32_t, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
-        else hipLaunchKernelGGL((box_copy_kernel<uint16_t, 4>), grid, dim3(BOX_THREADS), 0, stream, p);
+        if (vb == 16) launch_copy<u32x4>(p, grid, unroll, stream);
+        else if (vb == 8) launch_copy<u32x2>(p, grid, 4, stream);
+        else if (vb == 4) launch_copy<uint32_t>(p, grid, 4, stream);
+        else launch_copy<uint16_t>(p, grid, 4, stream);
     }
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }

@@ -59,6 +59,7 @@ struct GemmPlan {
 };
 
 int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream);
+void set_tile_order(int32_t order);
 
 // ---------------------------------------------------------------------------------------------
 // Row statistics of the model-parallel softmax.
