@@ -26,6 +26,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak, TFLOP/s
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak, GB/s
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
+# calibration copy; summary in profiles/bench_mlp_k8_counters.md).  Offline figures, not re-measured here.
+TRAFFIC_BYTES = {"gemm1": 1.900e9, "gemm2": 3.491e9, "boxing_p2b": 2.147e9}
 
 
 def parse():
@@ -181,10 +184,11 @@ def main():
             "input_gen_s": round(gen_s, 2),
         },
         "roofline": {"bound": "mfma", "kernel": dom_name, "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4),
+                     "traffic": TRAFFIC_BYTES["gemm1" if dom == 0 else "gemm2"], "traffic_unit": "bytes per launch"},
         "roofline_boxing": {"bound": "hbm", "kernel": "sbp_boxing P(sum)->B", "achieved": round(box_gbps, 1),
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(box_gbps / PEAK_HBM_GBPS, 4),
-                            "traffic": None},
+                            "traffic": TRAFFIC_BYTES["boxing_p2b"], "traffic_unit": "bytes per launch"},
     }
 
     if not args.no_cpu_baseline:
