@@ -308,10 +308,6 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     // 1 GiB all2all 6.4 TB/s against 5.3 TB/s.
     int unroll = 1;
     int64_t cap_total = reduce ? 65536 : 131072;
-#ifdef SBP_EXPERIMENT
-    if (const char* e = getenv("SBP_BOX_UNROLL")) unroll = atoi(e);
-    if (const char* e = getenv("SBP_BOX_CAP")) cap_total = atoll(e);
-#endif
     int64_t bx = (max_units + (int64_t)BOX_THREADS * unroll - 1) / ((int64_t)BOX_THREADS * unroll);
     const int64_t cap = (cap_total + tasks - 1) / tasks;
     if (bx > cap) bx = cap;

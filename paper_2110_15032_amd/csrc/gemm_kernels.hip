@@ -40,8 +40,14 @@ __device__ inline float epilogue(float v) {
     else return v;
 }
 
-__device__ inline void store_out(float* c, int64_t pos, float v) { c[pos] = v; }
-__device__ inline void store_out(uint16_t* c, int64_t pos, float v) { c[pos] = f32_to_bf16(v); }
+// results are written once and not read again by this kernel: streaming (non-temporal) stores keep
+// them from displacing operand tiles in L2
+__device__ inline void store_out(float* c, int64_t pos, float v) {
+    __builtin_nontemporal_store(v, c + pos);
+}
+__device__ inline void store_out(uint16_t* c, int64_t pos, float v) {
+    __builtin_nontemporal_store(f32_to_bf16(v), c + pos);
+}
 
 // ------------------------------------------------------------------------------------------------
 // generic kernel
@@ -72,11 +78,6 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmPlan p) {
 // ------------------------------------------------------------------------------------------------
 // MFMA kernel
 // ------------------------------------------------------------------------------------------------
-// Timing experiments only: bit 0 no global loads, bit 1 no LDS reads in the loop, bit 2 no barrier,
-// bit 3 no scheduling hints.  A product build always has SBP_DBG == 0.
-#ifndef SBP_DBG
-#define SBP_DBG 0
-#endif
 
 constexpr int BK = 64;  // reduction extent of one LDS stage of gemm_mfma_kernel, in elements
 
@@ -262,9 +263,13 @@ __device__ inline float mfma_epilogue(float v) {
     else return v;
 }
 
-// Epilogue of both MFMA kernels.  D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r].
-// Compile-time tile indices: the accumulators must never be indexed dynamically (they would move
-// to scratch memory).  Interior tiles (uniform test) store without per-element guards.
+// Epilogue of both MFMA kernels.  D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r]: one store
+// instruction writes two full 128-byte row segments (fp32).  (Issuing the MFMAs with swapped operands
+// would give each lane four consecutive columns and 16-byte stores, but then a 128-byte line is
+// completed by four separate instructions; measured 5 % slower with cached and 30 % slower with
+// streaming stores, so the scalar-per-lane form stays.)  Compile-time tile indices: the accumulators
+// must never be indexed dynamically (they would move to scratch memory).  Interior tiles (uniform
+// test) store without per-element guards.
 template <int BM, int BN, int TM, int TN, int FM, int FN, int EPI, typename OutT>
 __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&acc)[FM][FN], const GemmShard& s, int m0, int n0, int wm, int wn, int lane) {
     OutT* C = static_cast<OutT*>(s.c);
@@ -296,7 +301,6 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
 // in underneath the matrix pipe instead of in a burst right before they are needed.
 template <int NMFMA, int NDS, int NVM>
 __device__ inline void pace() {
-    if constexpr (SBP_DBG & 8) return;
     static_for<NMFMA>([&](auto i) {
         constexpr int I = decltype(i)::value;
         constexpr int nds = NDS * (I + 1) / NMFMA - NDS * I / NMFMA;   // spread evenly, all before the phase ends
@@ -365,10 +369,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
     for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
 
     auto read_frags = [&](const char* sa, const char* sb, int ks, int slot) {
-        if constexpr (SBP_DBG & 2) {
-            if (ks != 100) return;   // experiment: only the priming read (ks == 100) touches LDS
-            ks = 0;
-        }
 #pragma unroll
         for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, lob, j, ks);
 #pragma unroll
@@ -393,10 +393,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
         const char* sb = CUR ? sB1 : sB0;
         char* da = CUR ? sA0 : sA1;
         char* db = CUR ? sB0 : sB1;
-        if constexpr (!(SBP_DBG & 1)) {
-            TA::load_direct(da, A, offa, wave);
-            TB::load_direct(db, B, offb, wave);
-        }
+        TA::load_direct(da, A, offa, wave);
+        TB::load_direct(db, B, offb, wave);
         ++t;
         const bool adv = t + 1 < steps;      // tile t + 1 exists (t already counts this step)
         A += adv ? stepa : 0u;
@@ -410,10 +408,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
         read_frags(sa, sb, 3, 1);
         mfmas(0);
         pace<FM * FN, NDS, 0>();
-        if constexpr (!(SBP_DBG & 4)) {
-            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): loads landed, fragment reads returned
-            __builtin_amdgcn_s_barrier();
-        }
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0): loads landed, fragment reads returned
+        __builtin_amdgcn_s_barrier();
         read_frags(da, db, 0, 0);
         mfmas(1);
         pace<FM * FN, NDS, 0>();
@@ -429,8 +425,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
         B += stepb;
     }
     __builtin_amdgcn_s_barrier();
-    read_frags(sA0, sB0, (SBP_DBG & 2) ? 100 : 0, 0);
-    if constexpr (SBP_DBG & 2) read_frags(sA0, sB0, 100, 1);
+    read_frags(sA0, sB0, 0, 0);
     for (int pair = 0; pair < steps / 2; ++pair) {
         step(I0{});
         step(I1{});
@@ -448,8 +443,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
 //   wait until only the loads of tiles t + 2 .. are outstanding (they complete in order), barrier
 //   read the fragments of (t + 1, ks = 0), run the MFMAs of (t, ks = 1)
 // ------------------------------------------------------------------------------------------------
+// Tiles of at most 256 x 128 on 4 waves are built to run TWO workgroups per CU (<= 256 registers per
+// lane, <= 80 KB LDS): while one stores its results the other keeps the matrix cores busy.
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int NST, int EPI, typename OutT>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_pipe_kernel(GemmPlan p, int tm, int tn, int order) {
+__global__ __launch_bounds__(WM * WN * 64, (BM * BN <= 256 * 128 && WM * WN == 4) ? 2 : 1) void gemm_mfma_pipe_kernel(GemmPlan p, int tm, int tn, int order) {
     constexpr int BKT = 32;
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -576,40 +573,211 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_pipe_kernel(GemmPlan p
     store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Persistent form of the pipelined kernel: one workgroup per CU walks its tiles v = b, b + G, ...
+// (G = grid size, a multiple of 8, so a workgroup stays on the XCD the tile walk assigns) and the
+// load stream never drains: the loads for the first stages of tile i + 1 are issued during the last
+// steps of tile i, so neither the prologue latency nor the workgroup turn-around (a new workgroup
+// cannot start before the old one's stores have drained) nor the output stores themselves stop the
+// matrix pipe for longer than it takes to ISSUE the stores.
+//
+// In-order vmcnt bookkeeping: step g issues the loads of stage g + NST - 1 and needs stage g + 1.
+// After an epilogue the store instructions of this wave sit between those two in the queue, so the
+// first NST - 2 steps of the next tile may leave up to (NST - 2) NVM + (stores) operations
+// outstanding; the counter saturates at 63, which is a valid (stricter) bound as long as the epilogue
+// issued at least 63 - (NST - 2) NVM stores per wave -- true for interior tiles (16 FM FN of them).
+// After an edge tile (guarded, fewer stores) everything is drained once instead.
+// Requires every shard's reduction extent to be a multiple of 32 NST.
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int NST, int EPI, typename OutT>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPlan p, int tm, int tn, int order, int nblk) {
+    constexpr int BKT = 32;
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int FM = TM / 32, FN = TN / 32;
+    constexpr int NDS = (A_KC ? FM : 2 * FM) + (B_KC ? FN : 2 * FN);
+    using TA = Tile<BM, A_KC, NT, BKT>;
+    using TB = Tile<BN, B_KC, NT, BKT>;
+    constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
+    constexpr int WAIT_KEEP = (NST - 2) * NVM;
+    static_assert(NST == 4, "written for four stages");
+    static_assert(16 * FM * FN >= 63 - WAIT_KEEP, "interior epilogue must issue enough stores for the saturated wait");
+    __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA2[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA3[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB2[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB3[TB::BYTES];
+    auto stA = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sA0; else if constexpr (I == 1) return sA1; else if constexpr (I == 2) return sA2; else return sA3;
+    };
+    auto stB = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sB0; else if constexpr (I == 1) return sB1; else if constexpr (I == 2) return sB2; else return sB3;
+    };
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int G = gridDim.x;
+
+    // first valid tile at or after virtual block v (uneven shards have fewer tiles than tm x tn)
+    auto next_valid = [&](int v) {
+        for (; v < nblk; v += G) {
+            const TileCoord tc = map_tile(v, nblk, tm, tn, p.groups, order);
+            if (tc.valid && tc.tile_m * BM < p.s[tc.g].m && tc.tile_n * BN < p.s[tc.g].n) break;
+        }
+        return v;
+    };
+
+    // ---- load cursor: always exactly NST - 1 stages ahead of the compute cursor ------------------
+    gbl_char* A = nullptr;
+    gbl_char* B = nullptr;
+    uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+    uint32_t stepa = 0, stepb = 0;
+    const int first = next_valid(blockIdx.x);
+    if (first >= nblk) return;         // nothing for this workgroup
+    auto open_tile = [&](int v) {
+        const TileCoord tc = map_tile(v, nblk, tm, tn, p.groups, order);
+        const GemmShard& s = p.s[tc.g];
+        A = (gbl_char*)s.a;
+        B = (gbl_char*)s.b;
+#pragma unroll
+        for (int it = 0; it < TA::PER_THREAD; ++it) offa[it] = TA::src_offset(s.lda, tc.tile_m * BM, s.m, it * NT + tid);
+#pragma unroll
+        for (int it = 0; it < TB::PER_THREAD; ++it) offb[it] = TB::src_offset(s.ldb, tc.tile_n * BN, s.n, it * NT + tid);
+        stepa = TA::step_bytes(s.lda);
+        stepb = TB::step_bytes(s.ldb);
+    };
+    open_tile(first);
+    // Branch-free: always NVM loads (the wait counts rely on it), then one stage forward.  Because a
+    // tile has a multiple of NST stages, the cursor leaves a tile exactly after step 0 of the tile's
+    // last round; the tile loop below re-opens it there.  Past the last tile the steps are zeroed, so
+    // the last stage is simply re-read (in bounds, never used).
+    auto issue = [&](char* da, char* db) {
+        TA::load_direct(da, A, offa, wave);
+        TB::load_direct(db, B, offb, wave);
+        A += stepa;
+        B += stepb;
+    };
+
+    // ---- compute side --------------------------------------------------------------------------
+    f32x16 acc[FM][FN];
+    bf16x8 fa[2][FM], fb[2][FN];
+    int loa[TA::template nlo<FM>()], lob[TB::template nlo<FN>()];
+#pragma unroll
+    for (int x = 0; x < TA::template nlo<FM>(); ++x) loa[x] = TA::lane_offset(x, wm * TM, lane);
+#pragma unroll
+    for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
+    auto read_frags = [&](const char* sa, const char* sb, int ks, int slot) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag(sb, lob, j, ks);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[slot][i] = TA::frag(sa, loa, i, ks);
+    };
+    auto mfmas = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int WAIT_STRICT = (WAIT_KEEP & 15) | ((WAIT_KEEP >> 4) << 14) | 0x0070;   // vmcnt(WAIT_KEEP) lgkmcnt(0)
+    // Stores of the previous tile's epilogue sit in the same in-order queue in front of the next
+    // loads, so the first step of a tile also waits for them.
+    auto step = [&](auto cur) {
+        constexpr int CUR = decltype(cur)::value;
+        using Nxt = std::integral_constant<int, (CUR + 1) % NST>;
+        using Dst = std::integral_constant<int, (CUR + NST - 1) % NST>;
+        issue(stA(Dst{}), stB(Dst{}));
+        read_frags(stA(cur), stB(cur), 1, 1);
+        mfmas(0);
+        pace<FM * FN, NDS, NVM>();
+        __builtin_amdgcn_s_waitcnt(WAIT_STRICT);
+        __builtin_amdgcn_s_barrier();
+        read_frags(stA(Nxt{}), stB(Nxt{}), 0, 0);
+        mfmas(1);
+        pace<FM * FN, NDS, 0>();
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+
+    static_for<NST - 1>([&](auto i) { issue(stA(i), stB(i)); });
+    __builtin_amdgcn_s_waitcnt(WAIT_STRICT);
+    __builtin_amdgcn_s_barrier();
+    read_frags(sA0, sB0, 0, 0);
+
+    for (int cv = first; cv < nblk;) {
+        const TileCoord tc = map_tile(cv, nblk, tm, tn, p.groups, order);
+        const GemmShard s = p.s[tc.g];
+        const int m0 = tc.tile_m * BM, n0 = tc.tile_n * BN;
+        const int rounds = s.kk / (BKT * NST);
+        const int nv = next_valid(cv + G);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        for (int r = 0; r < rounds; ++r) {
+            step(I0{});
+            if (r == rounds - 1) {
+                // the load cursor has issued this tile's last stage: move it to the next tile
+                if (nv < nblk) {
+                    open_tile(nv);
+                } else {
+                    A -= stepa;     // no next tile: keep re-reading the last stage
+                    B -= stepb;
+                    stepa = 0;
+                    stepb = 0;
+                }
+            }
+            step(I1{});
+            step(I2{});
+            step(I3{});
+        }
+        store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
+        cv = nv;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);   // trailing (unused) loads must land before LDS is released
+}
+
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    void (*kern)(GemmPlan, int, int, int);
-    if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
-    else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
     const int tm = (max_m + BM - 1) / BM, tn = (max_n + BN - 1) / BN;
     const int64_t tiles = (int64_t)tm * tn * plan.groups;
     const int64_t nblk = (tiles + 7) / 8 * 8;
     if (nblk > 0x7FFFFFFF) return SBP_ERR_UNSUPPORTED;
-#ifdef SBP_EXPERIMENT
-    // Timing experiment only (never in a product build): every operand row aliases row 0, so all
-    // loads stay in bounds and hit in cache.  Results are meaningless.
-    if (getenv("SBP_DEBUG_LD0")) {
-        GemmPlan q = plan;
-        for (int g = 0; g < q.groups; ++g) { q.s[g].lda = 0; q.s[g].ldb = 0; }
-        hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, q, tm, tn, g_tile_order);
-        return SBP_OK;
+    if constexpr (ODD >= 100) {   // persistent kernel, ODD - 100 stages
+        int cus = 256;
+        hipDeviceProp_t prop;
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+        int grid = cus / 8 * 8;
+        if (grid > nblk) grid = (int)nblk;
+        hipLaunchKernelGGL((gemm_mfma_persist_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 100, EPI, OutT>), dim3((uint32_t)grid),
+                           dim3(WM * WN * 64), 0, st, plan, tm, tn, g_tile_order & 0xFFFF, (int)nblk);
+        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
     }
-#endif
+    void (*kern)(GemmPlan, int, int, int);
+    if constexpr (ODD >= 100) kern = nullptr;
+    else if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
+    else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
     hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, g_tile_order);
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }
 
 template <int BM, int BN, int WM, int WN, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_layout(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-#ifdef SBP_EXPERIMENT_MIN
-    if (plan.a_kc && !plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
-    return SBP_ERR_UNSUPPORTED;
-#else
     if (plan.a_kc && plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, true, ODD, EPI, OutT>(plan, max_m, max_n, st);
     if (plan.a_kc) return launch_mfma_cfg<BM, BN, WM, WN, true, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
     if (plan.b_kc) return launch_mfma_cfg<BM, BN, WM, WN, false, true, ODD, EPI, OutT>(plan, max_m, max_n, st);
     return launch_mfma_cfg<BM, BN, WM, WN, false, false, ODD, EPI, OutT>(plan, max_m, max_n, st);
-#endif
 }
 
 // fp32 results carry no epilogue on this path (GeLU of a P(sum) partial is rejected upstream and
@@ -677,20 +845,20 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         }
         return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
     }
+    bool k128 = true;   // every local reduction a whole number of four-stage rounds
+    for (int g = 0; g < plan.groups; ++g)
+        if (plan.s[g].m && plan.s[g].n && plan.s[g].kk % 128) k128 = false;
     if (variant == 0) {
-        // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages; shapes that would leave
-        // most of such a tile empty take the 128 x 128 tile.
-        variant = (max_m > 128 && max_n > 128) ? 6 : 4;
+        // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages, as one persistent
+        // workgroup per compute unit when the reduction length allows it; shapes that would leave most
+        // of such a tile empty take the 128 x 128 tile.
+        variant = (max_m > 128 && max_n > 128) ? (k128 ? 12 : 6) : 4;
     }
     switch (variant) {
-        case 2: return launch_mfma_out<256, 256, 2, 2, 0>(plan, max_m, max_n, stream);
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
-#ifndef SBP_EXPERIMENT_MIN
         case 4: return launch_mfma_out<128, 128, 2, 2, 0>(plan, max_m, max_n, stream);
-#endif
-        case 5: return launch_mfma_out<256, 256, 2, 2, 4>(plan, max_m, max_n, stream);
         case 6: return launch_mfma_out<256, 256, 2, 4, 4>(plan, max_m, max_n, stream);
-        case 8: return launch_mfma_out<256, 256, 2, 4, 3>(plan, max_m, max_n, stream);
+        case 12: return k128 ? launch_mfma_out<256, 256, 2, 4, 104>(plan, max_m, max_n, stream) : SBP_ERR_UNSUPPORTED;
         default: return SBP_ERR_UNSUPPORTED;
     }
 }
