@@ -12,6 +12,11 @@ Inputs are seeded synthetic tensors, resident in HBM before the timed region.  P
 `value` is the matmul work of a step (2.199 TFLOP) divided by the time of the whole step (boxing
 included); the per-kernel figures are in "kernels", "roofline" (dominant kernel) and
 "roofline_boxing".  The CPU oracle is timed on a bounded sample of the same workload.
+
+`--workload dp_grad | classifier | relayout` times the other full-size workloads the same way (one
+JSON line each, per-kernel times in "kernels", no oracle leg): the data-parallel weight gradient with
+its reduce-scatter / all-reduce, the model-parallel classifier head with its softmax statistics, and
+the pure relayout chain S(0) -> S(1) -> B -> S(0) on 16 logical devices.
 """
 from __future__ import annotations
 
@@ -41,6 +46,8 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=2, help="GEMM tile walk knob (default 2)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout"],
+                    help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
                          "1 GiB fp32 tensor: 1 GiB read + 1 GiB written) so that a counter run has a reference dispatch")
@@ -65,6 +72,12 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload != "mlp":
+        sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, args.variant)
+        sbp.sbp_set_knob(sbp.KNOB_TILE_ORDER, args.tile_order)
+        out = OTHER_WORKLOADS[args.workload](args, CONFIGS[args.workload], sbp, wl, torch, np)
+        print(json.dumps(out), flush=True)
+        return
     cfg = CONFIGS["mlp"]
     k = cfg["k"]
     T, D = cfg["X"]["shape"]          # 8192 tokens, 4096 model width
@@ -194,6 +207,183 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, k, args.cpu_rows, seed)
     print(json.dumps(out), flush=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# The other full-size workloads
+# ------------------------------------------------------------------------------------------------
+def make_arena(torch, np, stagger):
+    """k shard buffers carved from one allocation with `stagger` bytes between them (see main)."""
+    def arena(shapes, dtype):
+        esz = torch.empty((), dtype=dtype).element_size()
+        sizes = [int(np.prod(sh)) for sh in shapes]
+        step = [((n * esz + stagger + 255) // 256 * 256) // esz for n in sizes]
+        buf = torch.empty(sum(step) + 64, dtype=dtype, device="cuda")
+        out, off = [], 0
+        for sh, n, st in zip(shapes, sizes, step):
+            out.append(buf[off:off + n].view(*sh))
+            off += st
+        return out
+    return arena
+
+
+def time_stages(torch, stages_of, steps, warmup):
+    """stages_of(s) -> list of callables for step s.  Returns (avg ms per stage, wall ms per step)."""
+    stream = torch.cuda.current_stream()
+    for s in range(warmup):
+        for f in stages_of(s):
+            f(stream)
+    torch.cuda.synchronize()
+    n = len(stages_of(0))
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        evs[s][0].record(stream)
+        for i, f in enumerate(stages_of(warmup + s)):
+            f(stream)
+            evs[s][i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / steps for i in range(n)], wall
+
+
+def result_line(args, workload, k, value, unit, wall_ms, kernels, roofline):
+    return {"metric": f"SBP matmul TFLOP/s (% MFMA peak) + boxing GB/s (% HBM peak), k={k}",
+            "value": round(value, 3), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic", "config": {"workload": workload, "k": k, "gemm_variant": args.variant},
+            "kernels": kernels, "roofline": roofline}
+
+
+def bench_dp_grad(args, cfg, sbp, wl, torch, np):
+    """dW = X^T dY on 8 token shards -> 8 fp32 partials; P(sum) -> S(0) and P(sum) -> B.  The
+    tensors are about the size of the memory-side cache, so the step rotates over three buffer sets."""
+    k = cfg["k"]
+    Tk, Din = cfg["X"]["shape"]
+    Dout = cfg["dY"]["shape"][1]
+    arena = make_arena(torch, np, args.stagger)
+    seed = wl.SEED_BASE
+    sets = []
+    for r in range(3):
+        x_sh = arena([(Tk // k, Din)] * k, torch.int16)
+        dy_sh = arena([(Tk // k, Dout)] * k, torch.int16)
+        for i in range(k):
+            rows = np.arange(*wl.split_range(Tk, k, i))
+            for dst, spec in ((x_sh[i], cfg["X"]), (dy_sh[i], cfg["dY"])):
+                v = wl.normal(seed + r, spec["id"], spec["shape"], spec["dist"][1], rows, None, dtype=np.float32)
+                dst.copy_(torch.from_numpy(wl.to_bf16_bits(v).view(np.int16)))
+        XT = sbp.SbpTensor(x_sh, Din, Tk, sbp.BF16, trans=1)
+        DY = sbp.SbpTensor(dy_sh, Tk, Dout, sbp.BF16)
+        DW = sbp.SbpTensor(arena([(Din, Dout)] * k, torch.float32), Din, Dout, sbp.F32)
+        DWS = sbp.SbpTensor(arena([(Din // k, Dout)] * k, torch.float32), Din, Dout, sbp.F32)
+        DWB = sbp.SbpTensor(arena([(Din, Dout)] * k, torch.float32), Din, Dout, sbp.F32)
+        sets.append((XT, DY, DW, DWS, DWB))
+
+    def stages_of(s):
+        XT, DY, DW, DWS, DWB = sets[s % 3]
+        return [lambda st: sbp.sbp_matmul(XT, sbp.S(1), DY, sbp.S(0), DW, sbp.P_SUM, k, st),
+                lambda st: sbp.sbp_boxing(DW, sbp.P_SUM, DWS, sbp.S(0), k, st),
+                lambda st: sbp.sbp_boxing(DW, sbp.P_SUM, DWB, sbp.B, k, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    flops = 2.0 * Din * Tk * Dout
+    b_p2s, b_p2b = (k + 1) * Din * Dout * 4.0, 2.0 * k * Din * Dout * 4.0
+    tf = flops / (ms[0] * 1e-3) / 1e12
+    kernels = {"gemm_tn_psum_ms": round(ms[0], 4), "gemm_tflops": round(tf, 2),
+               "boxing_p2s_ms": round(ms[1], 4), "boxing_p2s_gbps": round(b_p2s / ms[1] / 1e6, 1),
+               "boxing_p2b_ms": round(ms[2], 4), "boxing_p2b_gbps": round(b_p2b / ms[2] / 1e6, 1),
+               "buffer_sets_rotated": 3}
+    roof = {"bound": "mfma", "kernel": "sbp_matmul (S1,S0)->P(sum), transposed X", "achieved": round(tf, 2),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "data-parallel weight gradient, k=8: dW = X^T dY, X[16384,1024] S(0) stored by tokens, "
+                             "dY[16384,4096] S(0) -> 8 fp32 partials [1024,4096]; boxing P->S(0) and P->B",
+                       k, flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
+
+
+def bench_classifier(args, cfg, sbp, wl, torch, np):
+    """logits = F W on 8 class shards (bf16), local row max -> P(max) -> B, local sum of exp -> P(sum) -> B."""
+    k = cfg["k"]
+    R, Dm = cfg["F"]["shape"]
+    C = cfg["W"]["shape"][1]
+    Ci = C // k
+    arena = make_arena(torch, np, args.stagger)
+    seed = wl.SEED_BASE
+
+    def bits(spec, rows=None, cols=None):
+        v = wl.normal(seed, spec["id"], spec["shape"], spec["dist"][1], rows, cols, dtype=np.float32)
+        return torch.from_numpy(wl.to_bf16_bits(v).view(np.int16))
+
+    f_sh = arena([(R, Dm)] * k, torch.int16)
+    f0 = bits(cfg["F"])
+    for t in f_sh:
+        t.copy_(f0)
+    w_sh = arena([(Dm, Ci)] * k, torch.int16)
+    for i in range(k):
+        w_sh[i].copy_(bits(cfg["W"], cols=np.arange(*wl.split_range(C, k, i))))
+    l_sh = arena([(R, Ci)] * k, torch.int16)
+    vec = lambda: arena([(R, 1)] * k, torch.float32)      # noqa: E731
+    Ft, Wt = sbp.SbpTensor(f_sh, R, Dm, sbp.BF16), sbp.SbpTensor(w_sh, Dm, C, sbp.BF16)
+    L = sbp.SbpTensor(l_sh, R, C, sbp.BF16)
+    MP, MB, SP, SB = (sbp.SbpTensor(vec(), R, 1, sbp.F32) for _ in range(4))
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_matmul(Ft, sbp.B, Wt, sbp.S(1), L, sbp.S(1), k, st),
+                lambda st: sbp.sbp_row_max(L, sbp.S(1), MP, k, st),
+                lambda st: sbp.sbp_boxing(MP, sbp.P_MAX, MB, sbp.B, k, st),
+                lambda st: sbp.sbp_row_sumexp(L, sbp.S(1), MB, SP, k, st),
+                lambda st: sbp.sbp_boxing(SP, sbp.P_SUM, SB, sbp.B, k, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    flops = 2.0 * R * Dm * C
+    lbytes = 2.0 * R * C
+    gbytes = lbytes + 2.0 * Dm * C + 2.0 * R * Dm       # logits written, W and F read once
+    tf = flops / (ms[0] * 1e-3) / 1e12
+    kernels = {"gemm_logits_ms": round(ms[0], 4), "gemm_tflops": round(tf, 2),
+               "gemm_algorithmic_gbps": round(gbytes / ms[0] / 1e6, 1),
+               "row_max_ms": round(ms[1], 4), "row_max_gbps": round(lbytes / ms[1] / 1e6, 1),
+               "boxing_pmax_us": round(ms[2] * 1e3, 1),
+               "row_sumexp_ms": round(ms[3], 4), "row_sumexp_gbps": round(lbytes / ms[3] / 1e6, 1),
+               "boxing_psum_us": round(ms[4] * 1e3, 1)}
+    roof = {"bound": "mfma", "kernel": "sbp_matmul (B,S1)->S1 bf16 logits", "achieved": round(tf, 2),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "model-parallel classifier head, k=8: F[1024,512] B x W[512,1000000] S(1) -> bf16 logits S(1); "
+                             "row max P(max)->B; sum exp(L - max) P(sum)->B",
+                       k, flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
+
+
+def bench_relayout(args, cfg, sbp, wl, torch, np):
+    """S(0) -> S(1) (all2all), S(1) -> B (all-gather), B -> S(0) (local slice) on 16 logical devices."""
+    k = cfg["k"]
+    R, C = cfg["T"]["shape"]
+    Rk, Ck = R // k, C // k
+    arena = make_arena(torch, np, args.stagger)
+    s0 = arena([(Rk, C)] * k, torch.int16)
+    for i in range(k):
+        s0[i].copy_(torch.from_numpy(wl.pattern_u16((R, C), rows=np.arange(i * Rk, (i + 1) * Rk)).view(np.int16)))
+    s1 = arena([(R, Ck)] * k, torch.int16)
+    b = arena([(R, C)] * k, torch.int16)
+    o = arena([(Rk, C)] * k, torch.int16)
+    T0, T1, TB, TO = (sbp.SbpTensor(x, R, C, sbp.BF16) for x in (s0, s1, b, o))
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_boxing(T0, sbp.S(0), T1, sbp.S(1), k, st),
+                lambda st: sbp.sbp_boxing(T1, sbp.S(1), TB, sbp.B, k, st),
+                lambda st: sbp.sbp_boxing(TB, sbp.B, TO, sbp.S(0), k, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    t = 2.0 * R * C
+    by = [2 * t, (1 + k) * t, 2 * t]
+    g = [by[i] / ms[i] / 1e6 for i in range(3)]
+    kernels = {"s0_to_s1_ms": round(ms[0], 4), "s0_to_s1_gbps": round(g[0], 1),
+               "s1_to_b_ms": round(ms[1], 4), "s1_to_b_gbps": round(g[1], 1),
+               "b_to_s0_ms": round(ms[2], 4), "b_to_s0_gbps": round(g[2], 1)}
+    roof = {"bound": "hbm", "kernel": "sbp_boxing S(1)->B (1 GiB read, 16 GiB written)", "achieved": round(g[1], 1),
+            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g[1] / PEAK_HBM_GBPS, 4), "traffic": None}
+    return result_line(args, "relayout boxing, k=16: T[65536,8192] 16-bit words, S(0)->S(1), S(1)->B, B->S(0)",
+                       k, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
+
+
+OTHER_WORKLOADS = {"dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout}
 
 
 def cpu_baseline(cfg, k, rows, seed):

@@ -20,15 +20,19 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// fp32 -> bf16, round to nearest even, NaN kept quiet
-__device__ inline uint16_t f32_to_bf16(float f) {
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
-    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+// fp32 -> bf16, round to nearest even, NaN kept quiet: the hardware conversion (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+// two values into one dword, `lo` in the low half
+__device__ inline uint32_t f32_to_bf16x2(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // 0.5 x (1 + erf(x / sqrt 2)) written with erfc so that the negative tail keeps its relative accuracy
@@ -233,28 +237,26 @@ __device__ inline TileCoord map_tile(int bid, int nblk, int tm, int tn, int grou
     return t;
 }
 
-// erfc(z) for z >= 0 as t * exp(-z^2 + P(t)), t = 1 / (1 + z / 2): the Chebyshev fit published in
-// Numerical Recipes ("erfcc"), fractional error below 1.2e-7 for every z, so the negative tail of
-// GeLU keeps its relative accuracy.  Branch-free: one rcp, one exp, ten FMAs.
-__device__ inline float erfc_pos(float z) {
-    const float t = __frcp_rn(1.0f + 0.5f * z);
-    float p = 0.17087277f;
-    p = fmaf(p, t, -0.82215223f);
-    p = fmaf(p, t, 1.48851587f);
-    p = fmaf(p, t, -1.13520398f);
-    p = fmaf(p, t, 0.27886807f);
-    p = fmaf(p, t, -0.18628806f);
-    p = fmaf(p, t, 0.09678418f);
-    p = fmaf(p, t, 0.37409196f);
-    p = fmaf(p, t, 1.00002368f);
-    p = fmaf(p, t, -1.26551223f);
-    return t * __expf(fmaf(-z, z, p));
-}
-// gelu(x) = 0.5 x erfc(-x / sqrt 2)
+// gelu(x) = 0.5 x erfc(-x / sqrt 2), with erfc(z) = t 2^(-z^2 log2 e + P(t)), t = 1 / (1 + z / 2), for
+// z = |x| / sqrt 2 >= 0.  This is the form of the classic Chebyshev fit of erfc ("erfcc" in Numerical
+// Recipes), which keeps its RELATIVE accuracy in the tail, so gelu of a negative argument does too.
+// P is a degree-5 minimax fit of log2(erfc(z) e^(z^2) / t) on 0 <= z <= 14 made for this kernel (the
+// published fit has degree 9 and 1e-7; this one costs four FMAs less).  Relative error of gelu below
+// 2.2e-5 for every x, a hundredth of a bf16 rounding step.  One rcp, one exp2, eight FMA/mul, no branch.
+// The argument is clamped to +-14 (erfc underflows before that), so +-inf give +inf and -0.
 __device__ inline float gelu_fast(float x) {
-    const float z = x * -0.70710678118654752f;
-    const float e = erfc_pos(fabsf(z));
-    return 0.5f * x * (z >= 0.0f ? e : 2.0f - e);
+    const float xc = __builtin_amdgcn_fmed3f(x, -14.0f, 14.0f);
+    const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(xc), 0.35355339059327373f, 1.0f));
+    float p = 0.320185989f;
+    p = fmaf(p, t, -0.994857252f);
+    p = fmaf(p, t, 0.654060185f);
+    p = fmaf(p, t, 0.382378936f);
+    p = fmaf(p, t, 1.46516109f);
+    p = fmaf(p, t, -1.82694018f);
+    const float w = xc * 0.84932180028801905f;               // sqrt(log2(e) / 2): w^2 = z^2 log2 e
+    const float e = t * __builtin_amdgcn_exp2f(fmaf(-w, w, p));   // erfc(|x| / sqrt 2)
+    const float h = 0.5f * xc * e;
+    return x < 0.0f ? h : x - h;                             // x >= 0: 0.5 x (2 - erfc) = x - h
 }
 
 template <int EPI>
@@ -263,36 +265,104 @@ __device__ inline float mfma_epilogue(float v) {
     else return v;
 }
 
-// Epilogue of both MFMA kernels.  D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32] = acc[r]: one store
-// instruction writes two full 128-byte row segments (fp32).  (Issuing the MFMAs with swapped operands
-// would give each lane four consecutive columns and 16-byte stores, but then a 128-byte line is
-// completed by four separate instructions; measured 5 % slower with cached and 30 % slower with
-// streaming stores, so the scalar-per-lane form stays.)  Compile-time tile indices: the accumulators
-// must never be indexed dynamically (they would move to scratch memory).  Interior tiles (uniform
-// test) store without per-element guards.
+// Epilogue of the MFMA kernels.  A wave's accumulators hold D[8 (r / 4) + 4 (lane / 32) + r % 4][lane % 32]
+// = acc[r] for every 32 x 32 block: one column per lane.  Stored straight from there, a store
+// instruction would write 4 bytes (fp32) or 2 bytes (bf16) per lane, two short row segments at a time;
+// the memory pipeline takes 128 of those per wave and tile badly (with bf16 results and a short
+// reduction the epilogue then costs more than the multiplication).  Instead every wave passes its
+// results through a private 4 KB LDS window (STAGE_BYTES per wave, no workgroup barrier needed) that
+// turns them by 90 degrees: each lane then owns 16 consecutive bytes of a row, and one store
+// instruction writes eight complete 128-byte row segments.
+//   fp32: one 32 x 32 block at a time, row pitch 128 B.  Row R is kept at R ^ ((R >> 2) & 1): the two
+//         half-waves write rows R and R + 4 in one instruction and so land in different bank halves;
+//         the 16-byte reads of rows 2g, 2g + 1 by one 16-lane group do as well.
+//   bf16: one 32-row x 64-column strip at a time, row pitch 128 B.  Neighbouring lanes first swap one
+//         value (DPP quad permute) so that the even lane holds columns (c, c + 1) of row R and the odd
+//         lane columns (c - 1, c) of row R + 1, packed into one dword; the 64-byte half of the row that
+//         block j goes to is j ^ ((R >> 2) & 1), for the same bank reason.
+// Compile-time indices throughout: the accumulators must never be indexed dynamically (they would
+// move to scratch memory).  Edge tiles and result pitches that are not a multiple of 16 bytes take
+// the guarded element-wise path.
+constexpr int STAGE_BYTES = 4096;
+
 template <int BM, int BN, int TM, int TN, int FM, int FN, int EPI, typename OutT>
-__device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&acc)[FM][FN], const GemmShard& s, int m0, int n0, int wm, int wn, int lane) {
+__device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&acc)[FM][FN], const GemmShard& s, int m0, int n0, int wm, int wn, int lane, char* stage) {
     OutT* C = static_cast<OutT*>(s.c);
+    constexpr int EPV = 16 / (int)sizeof(OutT);   // elements per 16-byte store
+    const bool whole = m0 + BM <= s.m && n0 + BN <= s.n && s.ldc % EPV == 0;
+    if (whole) {
+        const int wave = (int)(threadIdx.x >> 6);
+        const int h = lane >> 5, c = lane & 31;
+        // lane parts of the LDS offsets, opaque so that every address is object + (lane part + constant)
+        int rd = wave * STAGE_BYTES + (((lane >> 3) ^ h) * 128) + (lane & 7) * 16;
+        if constexpr (sizeof(OutT) == 2) rd = wave * STAGE_BYTES + (lane >> 3) * 128 + (((lane & 7) * 16) ^ (64 * h));
+        asm volatile("" : "+v"(rd));
+        OutT* cg = C + (int64_t)(m0 + wm * TM + (lane >> 3)) * s.ldc + (n0 + wn * TN + (lane & 7) * EPV);
+        if constexpr (sizeof(OutT) == 4) {
+            int w0 = wave * STAGE_BYTES + h * 640 + c * 4;   // rows with r % 4 even: (b ^ h) = b + h
+            int w1 = wave * STAGE_BYTES + h * 384 + c * 4;   // rows with r % 4 odd:  (b ^ h) = b - h
+            asm volatile("" : "+v"(w0));
+            asm volatile("" : "+v"(w1));
+            static_for<FM * FN>([&](auto idx) {
+                constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
+                static_for<16>([&](auto ridx) {
+                    constexpr int r = decltype(ridx)::value;
+                    constexpr int off = (8 * (r >> 2) + (r & 3)) * 128;
+                    *reinterpret_cast<float*>(stage + (((r & 1) ? w1 : w0) + off)) = mfma_epilogue<EPI>(acc[i][j][r]);
+                });
+                __builtin_amdgcn_wave_barrier();
+                static_for<4>([&](auto qidx) {
+                    constexpr int q = decltype(qidx)::value;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(stage + (rd + q * 1024));
+                    __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + j * 32));
+                });
+                __builtin_amdgcn_wave_barrier();
+            });
+        } else {
+            static_assert(FN % 2 == 0, "bf16 results are staged in strips of two 32-column blocks");
+            const int odd = lane & 1;
+            int w0 = wave * STAGE_BYTES + (4 * h + odd) * 128 + h * 64 + (c >> 1) * 4;         // block j even
+            int w1 = wave * STAGE_BYTES + (4 * h + odd) * 128 + (1 - h) * 64 + (c >> 1) * 4;   // block j odd
+            asm volatile("" : "+v"(w0));
+            asm volatile("" : "+v"(w1));
+            static_for<FM * (FN / 2)>([&](auto idx) {
+                constexpr int i = decltype(idx)::value / (FN / 2), jp = decltype(idx)::value % (FN / 2);
+                static_for<2>([&](auto jidx) {
+                    constexpr int j = 2 * jp + decltype(jidx)::value;
+                    static_for<8>([&](auto pidx) {
+                        constexpr int r = 2 * decltype(pidx)::value;             // rows R (r) and R + 1 (r + 1)
+                        const float v0 = mfma_epilogue<EPI>(acc[i][j][r]);
+                        const float v1 = mfma_epilogue<EPI>(acc[i][j][r + 1]);
+                        const float send = odd ? v0 : v1;
+                        const float recv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+                        const uint32_t packed = f32_to_bf16x2(odd ? recv : v0, odd ? v1 : recv);
+                        constexpr int off = (8 * (r >> 2) + (r & 3)) * 128;
+                        *reinterpret_cast<uint32_t*>(stage + (((j & 1) ? w1 : w0) + off)) = packed;
+                    });
+                });
+                __builtin_amdgcn_wave_barrier();
+                static_for<4>([&](auto qidx) {
+                    constexpr int q = decltype(qidx)::value;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + (rd + q * 1024));
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + jp * 64));
+                });
+                __builtin_amdgcn_wave_barrier();
+            });
+        }
+        return;
+    }
     const int cn = lane & 31, rm = 4 * (lane >> 5);
-    const bool whole = m0 + BM <= s.m && n0 + BN <= s.n;
     static_for<FM * FN>([&](auto idx) {
         constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
         const int n = n0 + wn * TN + j * 32 + cn;
         const int mb = m0 + wm * TM + i * 32 + rm;
         OutT* cp = C + (int64_t)mb * s.ldc + n;
-        if (whole) {
-            static_for<16>([&](auto ridx) {
-                constexpr int r = decltype(ridx)::value;
-                store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, mfma_epilogue<EPI>(acc[i][j][r]));
-            });
-        } else {
-            static_for<16>([&](auto ridx) {
-                constexpr int r = decltype(ridx)::value;
-                const int m = mb + 8 * (r >> 2) + (r & 3);
-                const float v = mfma_epilogue<EPI>(acc[i][j][r]);
-                if (m < s.m && n < s.n) store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
-            });
-        }
+        static_for<16>([&](auto ridx) {
+            constexpr int r = decltype(ridx)::value;
+            const int m = mb + 8 * (r >> 2) + (r & 3);
+            const float v = mfma_epilogue<EPI>(acc[i][j][r]);
+            if (m < s.m && n < s.n) store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+        });
     });
 }
 
@@ -333,6 +403,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
     __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
     __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
     __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sOut[WM * WN * STAGE_BYTES];   // epilogue windows, one per wave
 
     const TileCoord tc = map_tile(blockIdx.x, gridDim.x, tm, tn, p.groups, order);
     if (!tc.valid) return;
@@ -432,7 +503,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_kernel(GemmPlan p, int
     }
     if (steps & 1) step(I0{});
 
-    store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
+    store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -467,6 +538,7 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN <= 256 * 128 && WM * WN == 4
     __shared__ __attribute__((aligned(1024))) char sB2[TB::BYTES];
     __shared__ __attribute__((aligned(1024))) char sB3[NST > 3 ? TB::BYTES : 16];
     __shared__ __attribute__((aligned(1024))) char sB4[NST > 4 ? TB::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sOut[WM * WN * STAGE_BYTES];   // epilogue windows, one per wave
     auto stA = [&](auto i) -> char* {
         constexpr int I = decltype(i)::value;
         if constexpr (I == 0) return sA0; else if constexpr (I == 1) return sA1; else if constexpr (I == 2) return sA2;
@@ -570,7 +642,7 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN <= 256 * 128 && WM * WN == 4
     });
     __builtin_amdgcn_s_waitcnt(0x0070);   // drain the (unread) trailing loads before LDS is released
 
-    store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
+    store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -610,6 +682,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
     __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
     __shared__ __attribute__((aligned(1024))) char sB2[TB::BYTES];
     __shared__ __attribute__((aligned(1024))) char sB3[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sOut[WM * WN * STAGE_BYTES];   // epilogue windows, one per wave
     auto stA = [&](auto i) -> char* {
         constexpr int I = decltype(i)::value;
         if constexpr (I == 0) return sA0; else if constexpr (I == 1) return sA1; else if constexpr (I == 2) return sA2; else return sA3;
@@ -741,7 +814,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
             step(I2{});
             step(I3{});
         }
-        store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane);
+        store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
         cv = nv;
     }
     __builtin_amdgcn_s_waitcnt(0x0070);   // trailing (unused) loads must land before LDS is released
