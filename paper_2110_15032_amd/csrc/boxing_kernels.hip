@@ -8,7 +8,8 @@
 //
 //   P -> B        1 task : all k sources, all k destinations, whole tensor       (all-reduce)
 //   P -> S(a)     k tasks: all k sources at slice j        -> out_j              (reduce-scatter)
-//   S(a) -> B     k tasks: in_i                            -> slice i of all k   (all-gather)
+//   S(a) -> B     k tasks: in_i                            -> slice i of all k   (all-gather; 16-byte
+//                          vectors take box_gather_bcast_kernel instead, see there)
 //   S(a) -> S(b)  k*k    : in_i restricted to slice j of b -> out_j at slice i   (all2all)
 //   B -> S(a)     k tasks: slice j of in_j (its own copy)  -> out_j              (local slice)
 //   X -> X        k tasks: in_i -> out_i                                         (identity)
@@ -204,6 +205,90 @@ __global__ __launch_bounds__(BOX_THREADS) void box_copy_kernel(BoxParams p) {
     }
 }
 
+// S(a) -> B (all-gather) at scale.  Writing every vector to all k destinations at once keeps k write
+// streams open across the chip, and HBM takes that badly (measured on 16 x 1 GiB: 5.1 TB/s, against
+// 6.9 TB/s for one stream).  So the logical tensor is cut into chunks of `pieces` x 4 KB and each chunk
+// is written to destination 0, then 1, ... by consecutive groups of workgroups:
+//     block id = (chunk * k + destination) * pieces + piece
+// At any time the chip then writes one or two contiguous runs.  The chunk is read k times, but only
+// the first read reaches HBM: with pieces a multiple of 8 a piece is handled by the same XCD in every
+// pass, and 8 MB chunks (1 MB per XCD) stay in its L2 (plain loads; the stores stream past it).
+// Sources are read-only, so the passes need no ordering among themselves.
+// The index arithmetic is kept off the per-vector path where it can be (an HBM-bound kernel has
+// about 80 lane-instructions per 16-byte vector to spend): block and row decomposition once per
+// workgroup, the owner of a position from a float estimate with a +-1 fix-up.  Measured on
+// 16 x 1 GiB: 6.3 TB/s with one vector per lane and 2048 pieces, 6.1 / 5.7 TB/s with two / four
+// vectors per lane at the same chunk size, so one it is.
+constexpr int BCAST_U = 1;
+template <typename V>
+__global__ __launch_bounds__(BOX_THREADS) void box_gather_bcast_kernel(BoxParams p, uint32_t log2_pieces, uint32_t total,
+                                                                        uint32_t q, uint32_t rem) {
+    __shared__ const V* sp[SBP_MAX_K];
+    if ((int)threadIdx.x < p.k) sp[threadIdx.x] = static_cast<const V*>(p.src[threadIdx.x]);
+    __syncthreads();
+    const uint32_t k = (uint32_t)p.k;
+    const uint32_t piece = blockIdx.x & ((1u << log2_pieces) - 1);
+    const uint32_t cj = blockIdx.x >> log2_pieces;
+    const uint32_t chunk = cj / k, j = cj - chunk * k;
+    const uint32_t idx0 = ((chunk << log2_pieces) + piece) * (uint32_t)(BOX_THREADS * BCAST_U);   // first vector of the piece
+    if (idx0 >= total) return;
+    const uint32_t vec = (uint32_t)p.vec_elems, lv = __builtin_ctz(vec);
+    const uint32_t cols_v = (uint32_t)(p.cols >> lv);
+    const uint32_t r0 = idx0 / cols_v, c0 = idx0 - r0 * cols_v;
+    // balanced split of the split axis: shards [0, rem) hold q + 1 indices, the rest q; edge = first index of the rest
+    const uint32_t edge = rem * (q + 1);
+    const float inv_hi = 1.0f / (float)(q + 1), inv_lo = 1.0f / (float)(q ? q : 1);
+    const bool by_rows = p.axis_in == 0;
+    V val[BCAST_U];
+    uint32_t pos[BCAST_U];
+#pragma unroll
+    for (int u = 0; u < BCAST_U; ++u) {
+        const uint32_t idx = idx0 + u * BOX_THREADS + threadIdx.x;
+        pos[u] = idx;
+        if (idx < total) {
+            uint32_t c = c0 + u * BOX_THREADS + threadIdx.x, r = r0;
+            if (cols_v >= (uint32_t)(BOX_THREADS * BCAST_U)) {   // a piece crosses at most one row boundary
+                if (c >= cols_v) {
+                    c -= cols_v;
+                    ++r;
+                }
+            } else {
+                const uint32_t w = c / cols_v;
+                r += w;
+                c -= w * cols_v;
+            }
+            const uint32_t x = by_rows ? r : c << lv;
+            // owner i of index x: quotient below 64, so the float estimate is off by one at most
+            uint32_t i, begin, len;
+            if (x < edge) {
+                i = (uint32_t)((float)x * inv_hi);
+                begin = i * (q + 1);
+                len = q + 1;
+            } else {
+                i = (uint32_t)((float)(x - edge) * inv_lo);
+                begin = edge + i * q;
+                i += rem;
+                len = q;
+            }
+            if (x < begin) {
+                --i;
+                len = q + (i < rem ? 1u : 0u);
+                begin -= len;
+            } else if (x >= begin + len) {
+                begin += len;
+                ++i;
+                len = q + (i < rem ? 1u : 0u);
+            }
+            const int64_t spos = by_rows ? (int64_t)(r - begin) * cols_v + c : ((int64_t)r * len + (x - begin)) >> lv;
+            val[u] = sp[i][spos];
+        }
+    }
+    V* __restrict__ dst = static_cast<V*>(p.dst[j]);
+#pragma unroll
+    for (int u = 0; u < BCAST_U; ++u)
+        if (pos[u] < total) __builtin_nontemporal_store(val[u], dst + pos[u]);
+}
+
 inline int64_t gcd64(int64_t a, int64_t b) {
     while (b) {
         const int64_t t = a % b;
@@ -302,10 +387,23 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     if (max_units >= (int64_t)1 << 31) return SBP_ERR_UNSUPPORTED;
 
     const bool reduce = p_in && plan.sbp_in != plan.sbp_out;
-    // Streaming kernels run fastest on this chip as many short-lived workgroups: one vector per lane
-    // and a grid that covers the data in one pass up to a cap.  Measured on the 8-way all-reduce of
-    // 1 GiB: 5.99 TB/s this way against 5.1-5.4 TB/s for a 2048-block grid-stride loop; on the
-    // 1 GiB all2all 6.4 TB/s against 5.3 TB/s.
+    const int vbytes = p.vec_elems * plan.elem_bytes;
+    const int64_t total_v = plan.rows * plan.cols / g;
+    if (p.mode == M_S2B && plan.k > 1 && vbytes == 16 && plan.cols % g == 0 && total_v < ((int64_t)1 << 31) &&
+        plan.rows < ((int64_t)1 << 31) && plan.cols < ((int64_t)1 << 31)) {
+        const int64_t per_piece = (int64_t)BOX_THREADS * BCAST_U;                 // 4 KB
+        const int64_t need = (total_v + per_piece - 1) / per_piece;
+        uint32_t lp = 3;                                                         // 8 .. 2048 pieces per chunk (8 MB)
+        while (lp < 11 && ((int64_t)1 << lp) < need) ++lp;
+        const int64_t chunks = (need + ((int64_t)1 << lp) - 1) >> lp;
+        const int64_t blocks = (chunks * plan.k) << lp;
+        if (blocks < ((int64_t)1 << 31)) {
+            const int64_t n = p.axis_in == 0 ? plan.rows : plan.cols;
+            hipLaunchKernelGGL(box_gather_bcast_kernel<u32x4>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp,
+                               (uint32_t)total_v, (uint32_t)(n / plan.k), (uint32_t)(n % plan.k));
+            return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        }
+    }
     int unroll = 1;
     int64_t cap_total = reduce ? 65536 : 131072;
     int64_t bx = (max_units + (int64_t)BOX_THREADS * unroll - 1) / ((int64_t)BOX_THREADS * unroll);
@@ -318,7 +416,7 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
         if (plan.sbp_in == SBP_P_SUM) launch_reduce<BOX_SUM>(p, grid, unroll, stream);
         else launch_reduce<BOX_MAX>(p, grid, unroll, stream);
     } else {
-        const int vb = p.vec_elems * plan.elem_bytes;
+        const int vb = vbytes;
         if (vb == 16) launch_copy<u32x4>(p, grid, unroll, stream);
         else if (vb == 8) launch_copy<u32x2>(p, grid, 4, stream);
         else if (vb == 4) launch_copy<uint32_t>(p, grid, 4, stream);
