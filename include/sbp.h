@@ -121,8 +121,11 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w,
  *   S(a) -> S(b), a != b    all2all:         out_j = concat_i in_i[slice_j along b]
  *   B -> S(a)               local slice:     out_j = in_j[slice_j]  (its OWN copy)
  *   S(a)->S(a), B->B, P->P  identity copies
- *   S(a) -> P(sum), B -> P(sum)   zero-cost forms: every device keeps the values it
- *                           already holds and zero-fills the rest (B: device 0 keeps).
+ *   S(a) -> P(op), B -> P(op)     zero-cost forms: every device keeps the values it
+ *                           already holds, placed in a full-shape partial, and fills
+ *                           the rest with the identity of op (0 for sum, -inf for max);
+ *                           from B, device 0 keeps its copy and the others hold only
+ *                           the identity.
  * in->rows/cols/dtype must equal out's; P tensors must be SBP_F32; reductions are
  * done in fp32 in shard order i = 0 .. k-1, so every B copy is bit-identical and
  * runs are bit-reproducible.  S/B -> S/B moves raw words and never interprets

@@ -13,6 +13,7 @@
 //   S(a) -> S(b)  k*k    : in_i restricted to slice j of b -> out_j at slice i   (all2all)
 //   B -> S(a)     k tasks: slice j of in_j (its own copy)  -> out_j              (local slice)
 //   X -> X        k tasks: in_i -> out_i                                         (identity)
+//   S(a), B -> P  own kernel (box_to_partial_kernel): own values kept, identity elsewhere
 //
 // HBM-bound: every input byte is read once and every output byte written once, with the widest
 // vector (up to 16 B per lane) that all offsets and pitches of the conversion allow.
@@ -289,6 +290,41 @@ __global__ __launch_bounds__(BOX_THREADS) void box_gather_bcast_kernel(BoxParams
         if (pos[u] < total) __builtin_nontemporal_store(val[u], dst + pos[u]);
 }
 
+// S(a) -> P(op), B -> P(op) (Table 2 prices them at zero on the same devices): device j keeps what it
+// already holds, placed in the full-shape partial, and every other position gets the identity of
+// the reduction (0 / -inf).  B: device 0 keeps its copy, the others hold the identity only.
+// blockIdx.y = destination, the slow grid dimension, so the chip writes one destination at a time.
+template <typename V, bool MAXOP>
+__global__ __launch_bounds__(BOX_THREADS) void box_to_partial_kernel(BoxParams p, uint32_t total) {
+    const int32_t j = blockIdx.y;
+    const uint32_t lv = __builtin_ctz((uint32_t)p.vec_elems);
+    const uint32_t cols_v = (uint32_t)(p.cols >> lv);
+    int64_t rb = 0, rl = p.rows, cb = 0, cl = p.cols;
+    if (p.axis_in == 0) range_of(p.rows, p.k, j, 1, rb, rl);
+    if (p.axis_in == 1) range_of(p.cols, p.k, j, 1, cb, cl);
+    if (p.axis_in < 0 && j > 0) rl = 0;   // B: only device 0 contributes
+    const V* __restrict__ src = static_cast<const V*>(p.src[j]);
+    V* __restrict__ dst = static_cast<V*>(p.dst[j]);
+    V ident;
+    if constexpr (MAXOP) ident = V(-__builtin_inff());
+    else ident = V(0.0f);
+    const uint32_t stride = gridDim.x * BOX_THREADS;
+    for (uint32_t idx = blockIdx.x * BOX_THREADS + threadIdx.x; idx < total; idx += stride) {
+        const uint32_t r = idx / cols_v, c = idx - r * cols_v;
+        const int64_t x = (int64_t)c << lv;
+        V v = ident;
+        if ((int64_t)r >= rb && (int64_t)r < rb + rl && x >= cb && x < cb + cl)
+            v = __builtin_nontemporal_load(src + ((((int64_t)r - rb) * cl + (x - cb)) >> lv));
+        __builtin_nontemporal_store(v, dst + idx);
+    }
+}
+
+template <typename V>
+void launch_to_partial(const BoxParams& p, bool maxop, dim3 grid, uint32_t total, hipStream_t st) {
+    if (maxop) hipLaunchKernelGGL((box_to_partial_kernel<V, true>), grid, dim3(BOX_THREADS), 0, st, p, total);
+    else hipLaunchKernelGGL((box_to_partial_kernel<V, false>), grid, dim3(BOX_THREADS), 0, st, p, total);
+}
+
 inline int64_t gcd64(int64_t a, int64_t b) {
     while (b) {
         const int64_t t = a % b;
@@ -346,7 +382,28 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
         p.sbp_same = plan.sbp_in;
         tasks = plan.k;
     } else if (p_out) {
-        return SBP_ERR_UNSUPPORTED;  // S -> P, B -> P: zero-cost forms, not built yet
+        // S -> P, B -> P: own values kept, identity elsewhere
+        if (plan.elem_bytes != 4) return SBP_ERR_DTYPE;
+        int64_t g = 4;   // fp32 elements in 16 bytes
+        g = gcd64(g, plan.cols);
+        if (p.axis_in == 1)
+            for (int32_t i = 0; i < plan.k; ++i) {
+                g = gcd64(g, split_begin(plan.cols, plan.k, i));
+                g = gcd64(g, split_len(plan.cols, plan.k, i));
+            }
+        const int64_t total_v = plan.rows * plan.cols / g;
+        if (total_v == 0) return SBP_OK;
+        if (total_v >= ((int64_t)1 << 31)) return SBP_ERR_UNSUPPORTED;
+        p.vec_elems = (int32_t)g;
+        int64_t bx = (total_v + BOX_THREADS - 1) / BOX_THREADS;
+        const int64_t cap = (131072 + plan.k - 1) / plan.k;
+        if (bx > cap) bx = cap;
+        const dim3 grid((uint32_t)bx, (uint32_t)plan.k);
+        const bool maxop = plan.sbp_out == SBP_P_MAX;
+        if (g == 4) launch_to_partial<f32x4>(p, maxop, grid, (uint32_t)total_v, stream);
+        else if (g == 2) launch_to_partial<f32x2>(p, maxop, grid, (uint32_t)total_v, stream);
+        else launch_to_partial<float>(p, maxop, grid, (uint32_t)total_v, stream);
+        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
     } else if (p_in && plan.sbp_out == SBP_B) {
         p.mode = M_P2B;
         tasks = 1;

@@ -196,7 +196,6 @@ int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, 
     if ((is_partial(s_in) || is_partial(s_out)) && in->dtype != SBP_F32) return SBP_ERR_DTYPE;
     if (in->trans || out->trans) return SBP_ERR_UNSUPPORTED;
     if (is_partial(s_in) && is_partial(s_out) && s_in != s_out) return SBP_ERR_SIGNATURE;
-    if (s_out == SBP_P_MAX && !is_partial(s_in)) return SBP_ERR_UNSUPPORTED;
 
     std::vector<Span> ins, outs;
     spans_of(in, s_in, k, ins);

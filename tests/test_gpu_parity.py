@@ -90,6 +90,29 @@ def test_partial_value_boxing(k, op, so):
                 assert_bits_equal(got[j], got[0], f"B copies 0 and {j} of P({op})->B")
 
 
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("op", ["sum", "max"])
+@pytest.mark.parametrize("si", [orc.S0, orc.S1, orc.B])
+def test_boxing_into_partial_keeps_values_in_place(k, op, si):
+    """S(a) -> P and B -> P (priced at zero in Table 2): every device keeps its own values inside a
+    full-shape partial and holds the identity of the reduction elsewhere.  Bit-exact, and the
+    partials must reduce back to the global tensor."""
+    so = orc.P_SUM if op == "sum" else orc.P_MAX
+    for n, shape in enumerate(SHAPES + [(256, 1030)]):
+        T = rnd_f32(400 + n, shape)
+        ins = orc.scatter(T, si, k)
+        ref = orc.boxing(ins, si, so, k)                 # float64, exact images of the fp32 values
+        d_in = DevTensor.from_host(ins, *shape, si)
+        d_out = DevTensor.empty(*shape, np.float32, so, k)
+        sbp.sbp_boxing(d_in.desc, TO_ABI[si], d_out.desc, TO_ABI[so], k)
+        sync()
+        got = d_out.host()
+        for j in range(k):
+            assert got[j].shape == shape
+            assert np.array_equal(got[j].astype(np.float64), ref[j]), f"{si}->{so} k={k} shape={shape} shard {j}"
+        assert np.array_equal(orc.assemble([g.astype(np.float64) for g in got], so), T.astype(np.float64))
+
+
 def test_boxing_is_reproducible_run_to_run():
     k, shape = 8, (512, 640)
     parts = [rnd_f32(300 + i, shape) for i in range(k)]
