@@ -97,13 +97,16 @@ int32_t sbp_local_shape(int64_t rows, int64_t cols, sbp_t sbp, int32_t k, int32_
 
 /* Y = XW under SBP (Sec. 3.1, Table 1): every device i multiplies the local
  * tensors it holds, Y_i = X_i W_i, in ONE grouped launch over the k shards.
- *   x [M,K], w [K,N], y [M,N] global shapes; x and w share a dtype.
+ *   x [M,K], w [K,N], y [M,N] global shapes; x and w share a dtype (but see P(sum)
+ *   operands below).
  *   sbp_y must be the Table-1 result or SBP_AUTO.
  *   dtype of y: P(sum) results are always SBP_F32 (un-reduced partials keep the
  *   accumulator's precision); S / B results have the inputs' dtype.  bf16
  *   inputs accumulate in fp32 and round once, to nearest even.
- *   A P(sum) input operand (rows 4, 5 of Table 1) must be SBP_F32 and so must
- *   the other operand.
+ *   A P(sum) input operand (rows 4, 5 of Table 1) must be SBP_F32; the other
+ *   operand (B) may be SBP_F32 or SBP_BF16.  Next to a bf16 operand the fp32
+ *   partial is not rounded: it enters the matrix units as an exact sum of three
+ *   bf16 terms.
  *   k-way results are written to y->shard[i]; x, w are read only. */
 int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w, sbp_t sbp_w,
                    const sbp_tensor_t* y, sbp_t sbp_y, int32_t k, void* stream);

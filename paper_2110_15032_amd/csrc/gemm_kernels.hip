@@ -56,7 +56,8 @@ __device__ inline void store_out(uint16_t* c, int64_t pos, float v) {
 // ------------------------------------------------------------------------------------------------
 // generic kernel
 // ------------------------------------------------------------------------------------------------
-template <bool IN_BF16, typename OutT, int EPI>
+// A_BF16 / B_BF16: element type of each operand (a P(sum) operand is fp32 next to a bf16 one)
+template <bool A_BF16, bool B_BF16, typename OutT, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmPlan p) {
     const GemmShard s = p.s[blockIdx.z];
     const int m = blockIdx.y * 16 + threadIdx.y;
@@ -67,13 +68,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmPlan p) {
         const int64_t ia = p.a_kc ? (int64_t)m * s.lda + kk : (int64_t)kk * s.lda + m;
         const int64_t ib = p.b_kc ? (int64_t)n * s.ldb + kk : (int64_t)kk * s.ldb + n;
         float a, b;
-        if constexpr (IN_BF16) {
-            a = bf16_to_f32(static_cast<const uint16_t*>(s.a)[ia]);
-            b = bf16_to_f32(static_cast<const uint16_t*>(s.b)[ib]);
-        } else {
-            a = static_cast<const float*>(s.a)[ia];
-            b = static_cast<const float*>(s.b)[ib];
-        }
+        if constexpr (A_BF16) a = bf16_to_f32(static_cast<const uint16_t*>(s.a)[ia]);
+        else a = static_cast<const float*>(s.a)[ia];
+        if constexpr (B_BF16) b = bf16_to_f32(static_cast<const uint16_t*>(s.b)[ib]);
+        else b = static_cast<const float*>(s.b)[ib];
         acc = fmaf(a, b, acc);
     }
     store_out(static_cast<OutT*>(s.c), (int64_t)m * s.ldc + n, epilogue<EPI>(acc));
@@ -820,6 +818,187 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
     __builtin_amdgcn_s_waitcnt(0x0070);   // trailing (unused) loads must land before LDS is released
 }
 
+// ------------------------------------------------------------------------------------------------
+// Rows 4 and 5 of Table 1 next to bf16 tensors: one operand is an un-reduced P(sum) partial (fp32),
+// the other a bf16 B tensor, the result again fp32 partials.  Rounding the partial to bf16 would change
+// the sum it stands for, so it is split exactly into three bf16 terms on its way into LDS,
+//     x = hi + mid + lo,   hi = x cut to its top 16 bits, mid = (x - hi) cut likewise, lo = x - hi - mid
+// (each remainder is exact in fp32 and lo fits 8 significant bits), and every reduction step runs three
+// bf16 MFMAs, one per term, into the same fp32 accumulator.  Products of bf16 values are exact in
+// fp32, so the result differs from an fp32 GEMM by accumulation order only.  (Inf in the partial gives
+// NaN: inf - inf in the split.)
+// 128 x 128 tile, 4 waves of 64 x 64, two LDS stages of 32 reduction elements: three term tiles of the
+// fp32 operand (written from registers, same chunk order and swizzle as the direct-to-LDS image) and
+// one tile of the bf16 operand (direct to LDS).  F32_B: the fp32 operand is B (row 5), else A (row 4).
+// ------------------------------------------------------------------------------------------------
+struct SplitTerms { u32x4 hi, mid, lo; };
+__device__ inline SplitTerms split_f32x8(const f32x4 a, const f32x4 b) {
+    uint32_t h[8], m[8], l[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = e < 4 ? a[e] : b[e - 4];
+        h[e] = __float_as_uint(x) & 0xFFFF0000u;
+        const float r1 = x - __uint_as_float(h[e]);
+        m[e] = __float_as_uint(r1) & 0xFFFF0000u;
+        const float r2 = r1 - __uint_as_float(m[e]);
+        l[e] = __float_as_uint(r2);   // at most 8 significant bits: the low half is zero
+    }
+    SplitTerms t;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        t.hi[d] = (h[2 * d] >> 16) | h[2 * d + 1];
+        t.mid[d] = (m[2 * d] >> 16) | m[2 * d + 1];
+        t.lo[d] = (l[2 * d] >> 16) | (l[2 * d + 1] & 0xFFFF0000u);
+    }
+    return t;
+}
+
+template <bool A_KC, bool B_KC, bool F32_B>
+__global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int tn, int order) {
+    constexpr int BM = 128, BN = 128, WN = 2, NT = 256, BKT = 32;
+    constexpr int TM = 64, TN = 64, FM = 2, FN = 2;
+    using TA = Tile<BM, A_KC, NT, BKT>;
+    using TB = Tile<BN, B_KC, NT, BKT>;
+    using TF = std::conditional_t<F32_B, TB, TA>;   // tile type of the fp32 operand
+    using TH = std::conditional_t<F32_B, TA, TB>;   // ... of the bf16 operand
+    static_assert(TA::BYTES == TB::BYTES, "square tile");
+    __shared__ __attribute__((aligned(1024))) char sF0[3][TF::BYTES];   // hi, mid, lo
+    __shared__ __attribute__((aligned(1024))) char sF1[3][TF::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sH0[TH::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sH1[TH::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sOut[4 * STAGE_BYTES];
+
+    const TileCoord tc = map_tile(blockIdx.x, gridDim.x, tm, tn, p.groups, order);
+    if (!tc.valid) return;
+    const GemmShard s = p.s[tc.g];
+    const int m0 = tc.tile_m * BM, n0 = tc.tile_n * BN;
+    if (m0 >= s.m || n0 >= s.n) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // fp32 operand: 32 bytes per chunk (twice the bf16 byte offset); bf16 operand: direct to LDS
+    const char* F = static_cast<const char*>(F32_B ? s.b : s.a);
+    gbl_char* H = (gbl_char*)(F32_B ? s.a : s.b);
+    const int ldf = F32_B ? s.ldb : s.lda, ldh = F32_B ? s.lda : s.ldb;
+    uint64_t offf[TF::PER_THREAD];
+    uint32_t offh[TH::PER_THREAD];
+#pragma unroll
+    for (int it = 0; it < TF::PER_THREAD; ++it)
+        offf[it] = (uint64_t)2 * TF::src_offset(ldf, F32_B ? n0 : m0, F32_B ? s.n : s.m, it * NT + tid);
+#pragma unroll
+    for (int it = 0; it < TH::PER_THREAD; ++it) offh[it] = TH::src_offset(ldh, F32_B ? m0 : n0, F32_B ? s.m : s.n, it * NT + tid);
+    const uint64_t stepf = (uint64_t)2 * TF::step_bytes(ldf);
+    const uint32_t steph = TH::step_bytes(ldh);
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    int loa[TA::template nlo<FM>()], lob[TB::template nlo<FN>()];
+#pragma unroll
+    for (int x = 0; x < TA::template nlo<FM>(); ++x) loa[x] = TA::lane_offset(x, wm * TM, lane);
+#pragma unroll
+    for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
+
+    f32x4 raw[TF::PER_THREAD][2];
+    auto fetch = [&]() {   // global -> registers (fp32 operand), global -> LDS (bf16 operand)
+#pragma unroll
+        for (int it = 0; it < TF::PER_THREAD; ++it) {
+            const f32x4* g = reinterpret_cast<const f32x4*>(F + offf[it]);
+            raw[it][0] = g[0];
+            raw[it][1] = g[1];
+        }
+    };
+    auto stash = [&](char (*dst)[TF::BYTES]) {   // registers -> three term tiles
+#pragma unroll
+        for (int it = 0; it < TF::PER_THREAD; ++it) {
+            const SplitTerms t = split_f32x8(raw[it][0], raw[it][1]);
+            const int pos = (it * NT + tid) * 16;
+            *reinterpret_cast<u32x4*>(dst[0] + pos) = t.hi;
+            *reinterpret_cast<u32x4*>(dst[1] + pos) = t.mid;
+            *reinterpret_cast<u32x4*>(dst[2] + pos) = t.lo;
+        }
+    };
+    auto compute = [&](const char (*sf)[TF::BYTES], const char* sh) {
+#pragma unroll
+        for (int ks = 0; ks < BKT / 16; ++ks) {
+            if constexpr (F32_B) {
+                bf16x8 fa[FM];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) fa[i] = TA::frag(sh, loa, i, ks);
+#pragma unroll
+                for (int term = 0; term < 3; ++term)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        const bf16x8 fb = TB::frag(sf[term], lob, j, ks);
+#pragma unroll
+                        for (int i = 0; i < FM; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb, acc[i][j], 0, 0, 0);
+                    }
+            } else {
+                bf16x8 fb[FN];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) fb[j] = TB::frag(sh, lob, j, ks);
+#pragma unroll
+                for (int term = 0; term < 3; ++term)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i) {
+                        const bf16x8 fa = TA::frag(sf[term], loa, i, ks);
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
+                    }
+            }
+        }
+    };
+
+    const int steps = s.kk / BKT;
+    fetch();
+    TH::load_direct(sH0, H, offh, wave);
+    stash(sF0);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+    // stage names are compile-time in every step, so that the compiler can tell the direct-to-LDS
+    // load into one stage from the fragment reads of the other
+    auto step = [&](auto cur, bool more) {   // `more` is uniform
+        constexpr int CUR = decltype(cur)::value;
+        if (more) {
+            F += stepf;
+            H += steph;
+            fetch();
+            TH::load_direct(CUR ? sH0 : sH1, H, offh, wave);
+        }
+        compute(CUR ? sF1 : sF0, CUR ? sH1 : sH0);
+        if (more) stash(CUR ? sF0 : sF1);
+        __builtin_amdgcn_s_waitcnt(0x0070);   // this wave's direct-to-LDS loads have landed
+        __syncthreads();                      // next stage complete, this one free
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    for (int t = 0; t + 1 < steps; t += 2) {
+        step(I0{}, true);
+        step(I1{}, t + 2 < steps);
+    }
+    if (steps & 1) step(I0{}, false);
+    store_tile<BM, BN, TM, TN, FM, FN, SBP_EPI_NONE, float>(acc, s, m0, n0, wm, wn, lane, sOut);
+}
+
+template <bool F32_B>
+int32_t launch_split(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
+    const int tm = (max_m + 127) / 128, tn = (max_n + 127) / 128;
+    const int64_t nblk = ((int64_t)tm * tn * plan.groups + 7) / 8 * 8;
+    if (nblk > 0x7FFFFFFF) return SBP_ERR_UNSUPPORTED;
+    void (*kern)(GemmPlan, int, int, int);
+    if (plan.a_kc && plan.b_kc) kern = gemm_split_kernel<true, true, F32_B>;
+    else if (plan.a_kc) kern = gemm_split_kernel<true, false, F32_B>;
+    else if (plan.b_kc) kern = gemm_split_kernel<false, true, F32_B>;
+    else kern = gemm_split_kernel<false, false, F32_B>;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, g_tile_order);
+    return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+}
+
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
 int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
     const int tm = (max_m + BM - 1) / BM, tn = (max_n + BN - 1) / BN;
@@ -865,12 +1044,12 @@ int32_t launch_mfma_out(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
     return launch_mfma_layout<BM, BN, WM, WN, ODD, SBP_EPI_NONE, uint16_t>(plan, max_m, max_n, st);
 }
 
-template <bool IN_BF16, typename OutT>
+template <bool A_BF16, bool B_BF16, typename OutT>
 void launch_generic_epi(const GemmPlan& plan, dim3 grid, hipStream_t st) {
     if (plan.epilogue == SBP_EPI_GELU)
-        hipLaunchKernelGGL((gemm_generic_kernel<IN_BF16, OutT, SBP_EPI_GELU>), grid, dim3(16, 16), 0, st, plan);
+        hipLaunchKernelGGL((gemm_generic_kernel<A_BF16, B_BF16, OutT, SBP_EPI_GELU>), grid, dim3(16, 16), 0, st, plan);
     else
-        hipLaunchKernelGGL((gemm_generic_kernel<IN_BF16, OutT, SBP_EPI_NONE>), grid, dim3(16, 16), 0, st, plan);
+        hipLaunchKernelGGL((gemm_generic_kernel<A_BF16, B_BF16, OutT, SBP_EPI_NONE>), grid, dim3(16, 16), 0, st, plan);
 }
 
 // Shapes the MFMA kernel takes: whole 64-element reduction steps, 16-byte aligned rows.
@@ -891,6 +1070,24 @@ bool mfma_ok(const GemmPlan& plan) {
     return true;
 }
 
+// Shapes the split kernel takes: whole 32-element reduction steps, 16-byte aligned rows of both operands.
+bool split_ok(const GemmPlan& plan) {
+    if (plan.in_dtype != SBP_BF16 || plan.out_dtype != SBP_F32 || plan.epilogue != SBP_EPI_NONE) return false;
+    const bool fb = plan.f32_operand == 2;
+    for (int g = 0; g < plan.groups; ++g) {
+        const GemmShard& s = plan.s[g];
+        if (s.m == 0 || s.n == 0) continue;
+        if (s.kk == 0 || s.kk % 32) return false;
+        if ((fb ? s.lda : s.ldb) % 8 || (fb ? s.ldb : s.lda) % 4) return false;
+        if (!plan.a_kc && (s.m < 8 || (!fb && s.m % 4))) return false;
+        if (!plan.b_kc && (s.n < 8 || (fb && s.n % 4))) return false;
+        const int64_t ea = plan.a_kc ? (int64_t)s.m * s.lda : (int64_t)s.kk * s.lda;
+        const int64_t eb = plan.b_kc ? (int64_t)s.n * s.ldb : (int64_t)s.kk * s.ldb;
+        if (ea * 2 >= ((int64_t)1 << 32) || eb * 2 >= ((int64_t)1 << 32)) return false;
+    }
+    return true;
+}
+
 }  // namespace
 
 void set_tile_order(int32_t order) { g_tile_order = order; }
@@ -904,17 +1101,31 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
     }
     if (max_m == 0 || max_n == 0) return SBP_OK;   // every local product is empty
 
+    if (plan.f32_operand) {
+        // Table 1 rows 4 / 5 with a bf16 partner: split kernel, else the generic kernel with mixed element types
+        if (variant != 1 && split_ok(plan)) {
+            if (variant > 1) return SBP_ERR_UNSUPPORTED;
+            return plan.f32_operand == 2 ? launch_split<true>(plan, max_m, max_n, stream) : launch_split<false>(plan, max_m, max_n, stream);
+        }
+        if (variant > 1) return SBP_ERR_UNSUPPORTED;
+        const dim3 grid((max_n + 15) / 16, (max_m + 15) / 16, plan.groups);
+        if (grid.y > 65535 || grid.z > 65535) return SBP_ERR_UNSUPPORTED;
+        if (plan.out_dtype != SBP_F32 || plan.epilogue != SBP_EPI_NONE) return SBP_ERR_DTYPE;
+        if (plan.f32_operand == 2) launch_generic_epi<true, false, float>(plan, grid, stream);
+        else launch_generic_epi<false, true, float>(plan, grid, stream);
+        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    }
     const bool fast = mfma_ok(plan);
     if (variant == 1 || !fast) {
         if (variant > 1) return SBP_ERR_UNSUPPORTED;   // a forced MFMA variant cannot take this shape
         const dim3 grid((max_n + 15) / 16, (max_m + 15) / 16, plan.groups);
         if (grid.y > 65535 || grid.z > 65535) return SBP_ERR_UNSUPPORTED;
         if (plan.in_dtype == SBP_BF16) {
-            if (plan.out_dtype == SBP_F32) launch_generic_epi<true, float>(plan, grid, stream);
-            else launch_generic_epi<true, uint16_t>(plan, grid, stream);
+            if (plan.out_dtype == SBP_F32) launch_generic_epi<true, true, float>(plan, grid, stream);
+            else launch_generic_epi<true, true, uint16_t>(plan, grid, stream);
         } else {
             if (plan.out_dtype != SBP_F32) return SBP_ERR_DTYPE;
-            launch_generic_epi<false, float>(plan, grid, stream);
+            launch_generic_epi<false, false, float>(plan, grid, stream);
         }
         return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
     }

@@ -137,8 +137,15 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sb
     if ((st = check_tensor(w, sw, k)) != SBP_OK) return st;
     if ((st = check_tensor(y, sy, k)) != SBP_OK) return st;
     if (x->cols != w->rows || y->rows != x->rows || y->cols != w->cols) return SBP_ERR_SHAPE;
-    if (x->dtype != w->dtype) return SBP_ERR_DTYPE;
-    if ((is_partial(sx) || is_partial(sw)) && x->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    // a P(sum) operand is fp32; its partner may be fp32 or bf16 (rows 4 and 5 of Table 1 inside a bf16 graph)
+    int32_t f32_operand = 0;
+    if (is_partial(sx) && x->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    if (is_partial(sw) && w->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    if (x->dtype != w->dtype) {
+        if (is_partial(sx) && w->dtype == SBP_BF16) f32_operand = 1;
+        else if (is_partial(sw) && x->dtype == SBP_BF16) f32_operand = 2;
+        else return SBP_ERR_DTYPE;
+    }
     const int32_t want_out = is_partial(sy) ? SBP_F32 : x->dtype;
     if (y->dtype != want_out) return SBP_ERR_DTYPE;
     if (y->trans != 0) return SBP_ERR_UNSUPPORTED;
@@ -155,7 +162,8 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sb
 
     GemmPlan plan{};
     plan.groups = k;
-    plan.in_dtype = x->dtype;
+    plan.in_dtype = f32_operand ? SBP_BF16 : x->dtype;
+    plan.f32_operand = f32_operand;
     plan.out_dtype = y->dtype;
     plan.a_kc = x->trans ? 0 : 1;
     plan.b_kc = w->trans ? 1 : 0;

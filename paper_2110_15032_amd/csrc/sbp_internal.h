@@ -53,6 +53,7 @@ struct GemmPlan {
     GemmShard s[SBP_MAX_K];
     int32_t groups;
     int32_t in_dtype;   // SBP_F32 | SBP_BF16
+    int32_t f32_operand;  // 0: both operands have in_dtype; 1 / 2: A / B is an fp32 P(sum) partial next to a bf16 operand
     int32_t out_dtype;  // SBP_F32 | SBP_BF16
     int32_t a_kc, b_kc;
     int32_t epilogue;   // SBP_EPI_*

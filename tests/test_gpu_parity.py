@@ -213,6 +213,36 @@ def test_matmul_bf16_persistent_kernel(sx, sw, tx, tw, kshard):
         assert_matmul_close(g, ref[i], 2e-2, f"persistent ({sx},{sw}) trans=({tx},{tw}) shard {i}")
 
 
+@pytest.mark.parametrize("tx,tw", [(0, 0), (1, 0), (0, 1), (1, 1)])
+@pytest.mark.parametrize("row", [4, 5])
+@pytest.mark.parametrize("shape", [(296, 192, 328), (45, 100, 51)])
+def test_matmul_partial_fp32_times_bf16(row, tx, tw, shape):
+    """Table 1 rows 4 and 5 inside a bf16 graph: the P(sum) operand is k fp32 partials, its partner a
+    bf16 B tensor, the result k fp32 partials Y_i = X_i W (or X W_i).  The first shape takes the
+    MFMA kernel that splits the fp32 operand into three bf16 terms (several tiles, ragged edges),
+    the second the generic kernel.  Both keep fp32-GEMM accuracy: the partial is never rounded."""
+    k = 3
+    M, K, N = shape
+    X, W = rnd_f32(1, (M, K)), rnd_f32(2, (K, N))
+    if row == 4:
+        Xs = random_partials(10, X, k, "sum")
+        Wb = rnd_bf16(2, (K, N), 0.05)
+        Ws = orc.scatter(Wb, orc.B, k)
+        sx, sw = orc.P_SUM, orc.B
+        ref, sy = orc.matmul_sbp(Xs, sx, [values(w) for w in Ws], sw)
+    else:
+        Xb = rnd_bf16(1, (M, K))
+        Xs = orc.scatter(Xb, orc.B, k)
+        Ws = random_partials(40, W, k, "sum")
+        sx, sw = orc.B, orc.P_SUM
+        ref, sy = orc.matmul_sbp([values(x) for x in Xs], sx, Ws, sw)
+    assert sy == orc.P_SUM
+    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx, tw)
+    for i in range(k):
+        assert got[i].dtype == np.float32 and got[i].shape == ref[i].shape
+        assert_matmul_close(got[i], ref[i], 1e-5, f"row {row} trans=({tx},{tw}) shape={shape} partial {i}")
+
+
 def test_matmul_bf16_odd_shapes_fall_back():
     """pitches that are not multiples of 8 elements, K not a multiple of 64, uneven splits"""
     k = 3
