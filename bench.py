@@ -13,10 +13,11 @@ Inputs are seeded synthetic tensors, resident in HBM before the timed region.  P
 included); the per-kernel figures are in "kernels", "roofline" (dominant kernel) and
 "roofline_boxing".  The CPU oracle is timed on a bounded sample of the same workload.
 
-`--workload dp_grad | classifier | relayout` times the other full-size workloads the same way (one
-JSON line each, per-kernel times in "kernels", no oracle leg): the data-parallel weight gradient with
-its reduce-scatter / all-reduce, the model-parallel classifier head with its softmax statistics, and
-the pure relayout chain S(0) -> S(1) -> B -> S(0) on 16 logical devices.
+`--workload dp_grad | classifier | relayout | uvw` times the other full-size workloads the same way
+(one JSON line each, per-kernel times in "kernels", no oracle leg): the data-parallel weight gradient
+with its reduce-scatter / all-reduce, the model-parallel classifier head with its softmax statistics,
+the pure relayout chain S(0) -> S(1) -> B -> S(0) on 16 logical devices, and Y = U V W with the boxing
+deferred to the end against boxing right after the first product.
 """
 from __future__ import annotations
 
@@ -46,7 +47,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=2, help="GEMM tile walk knob (default 2)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -75,7 +76,7 @@ def main():
     if args.workload != "mlp":
         sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, args.variant)
         sbp.sbp_set_knob(sbp.KNOB_TILE_ORDER, args.tile_order)
-        out = OTHER_WORKLOADS[args.workload](args, CONFIGS[args.workload], sbp, wl, torch, np)
+        out = OTHER_WORKLOADS[args.workload](args, CONFIGS.get(args.workload), sbp, wl, torch, np)
         print(json.dumps(out), flush=True)
         return
     cfg = CONFIGS["mlp"]
@@ -383,7 +384,58 @@ def bench_relayout(args, cfg, sbp, wl, torch, np):
                        k, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
 
 
-OTHER_WORKLOADS = {"dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout}
+def bench_uvw(args, cfg, sbp, wl, torch, np):
+    """Y = U V W with U S(1), V S(0), W B (Sec. 3.3), bf16 inputs, k = 8.  Deferred boxing: (UV) stays
+    8 fp32 partials, each multiplied by W (Table 1 row 4), one P->B on Y.  Immediate boxing: P->B on
+    (UV), then the row-6 product.  Same matmul work either way; the boxed tensor is [M,N1] or [M,N2]."""
+    k = 8
+    M, K1, N1, N2 = 4096, 16384, 4096, 1024
+    arena = make_arena(torch, np, args.stagger)
+    seed = wl.SEED_BASE
+
+    def bits(tid, shape, std, rows=None, cols=None):
+        v = wl.normal(seed, tid, shape, std, rows, cols, dtype=np.float32)
+        return torch.from_numpy(wl.to_bf16_bits(v).view(np.int16))
+
+    u_sh = arena([(M, K1 // k)] * k, torch.int16)
+    v_sh = arena([(K1 // k, N1)] * k, torch.int16)
+    w_sh = arena([(N1, N2)] * k, torch.int16)
+    w0 = bits(102, (N1, N2), 0.02)
+    for i in range(k):
+        u_sh[i].copy_(bits(100, (M, K1), 1.0, cols=np.arange(*wl.split_range(K1, k, i))))
+        v_sh[i].copy_(bits(101, (K1, N1), 0.02, rows=np.arange(*wl.split_range(K1, k, i))))
+        w_sh[i].copy_(w0)
+    U, V, W = sbp.SbpTensor(u_sh, M, K1, sbp.BF16), sbp.SbpTensor(v_sh, K1, N1, sbp.BF16), sbp.SbpTensor(w_sh, N1, N2, sbp.BF16)
+    f32 = lambda r, c: sbp.SbpTensor(arena([(r, c)] * k, torch.float32), r, c, sbp.F32)      # noqa: E731
+    UV, UVB, YP, YL, YE = f32(M, N1), f32(M, N1), f32(M, N2), f32(M, N2), f32(M, N2)
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_matmul(U, sbp.S(1), V, sbp.S(0), UV, sbp.P_SUM, k, st),
+                lambda st: sbp.sbp_matmul(UV, sbp.P_SUM, W, sbp.B, YP, sbp.P_SUM, k, st),      # deferred
+                lambda st: sbp.sbp_boxing(YP, sbp.P_SUM, YL, sbp.B, k, st),
+                lambda st: sbp.sbp_boxing(UV, sbp.P_SUM, UVB, sbp.B, k, st),                   # immediate
+                lambda st: sbp.sbp_matmul(UVB, sbp.B, W, sbp.B, YE, sbp.B, k, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    f1, f2 = 2.0 * M * K1 * N1, 2.0 * k * M * N1 * N2
+    late, early = ms[0] + ms[1] + ms[2], ms[0] + ms[3] + ms[4]
+    kernels = {"gemm_uv_ms": round(ms[0], 4), "gemm_uv_tflops": round(f1 / ms[0] / 1e9, 2),
+               "late_gemm_partial_x_w_ms": round(ms[1], 4), "late_gemm_tflops": round(f2 / ms[1] / 1e9, 2),
+               "late_boxing_ms": round(ms[2], 4), "late_boxing_gbps": round(2.0 * k * M * N2 * 4 / ms[2] / 1e6, 1),
+               "early_boxing_ms": round(ms[3], 4), "early_boxing_gbps": round(2.0 * k * M * N1 * 4 / ms[3] / 1e6, 1),
+               "early_gemm_b_x_w_ms": round(ms[4], 4), "early_gemm_tflops": round(f2 / ms[4] / 1e9, 2),
+               "late_total_ms": round(late, 4), "early_total_ms": round(early, 4),
+               "max_abs_diff_late_vs_early": float((YL.keep[0] - YE.keep[0]).abs().max())}
+    tf = f2 / ms[1] / 1e9
+    roof = {"bound": "mfma", "kernel": "sbp_matmul (P(sum) fp32, B bf16)->P(sum): three bf16 MFMAs per product term",
+            "achieved": round(tf, 2), "peak": PEAK_BF16_TFLOPS / 3, "unit": "TFLOP/s (fp32-operand products)",
+            "frac": round(3 * tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "Y = U V W, k=8: U[4096,16384] S(1), V[16384,4096] S(0), W[4096,1024] B, bf16; boxing deferred "
+                             "(one P->B on Y) against immediate (P->B on UV)",
+                       k, (f1 + f2) / (late * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
+
+
+OTHER_WORKLOADS = {"dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw}
 
 
 def cpu_baseline(cfg, k, rows, seed):

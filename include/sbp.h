@@ -106,7 +106,9 @@ int32_t sbp_local_shape(int64_t rows, int64_t cols, sbp_t sbp, int32_t k, int32_
  *   A P(sum) input operand (rows 4, 5 of Table 1) must be SBP_F32; the other
  *   operand (B) may be SBP_F32 or SBP_BF16.  Next to a bf16 operand the fp32
  *   partial is not rounded: it enters the matrix units as an exact sum of three
- *   bf16 terms.
+ *   bf16 terms.  The same holds for row 6 when one B operand is SBP_F32 (a
+ *   partial that was boxed to B) and the other SBP_BF16; the result is then
+ *   SBP_F32.  Any other mix of dtypes is SBP_ERR_DTYPE.
  *   k-way results are written to y->shard[i]; x, w are read only. */
 int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w, sbp_t sbp_w,
                    const sbp_tensor_t* y, sbp_t sbp_y, int32_t k, void* stream);

@@ -142,11 +142,12 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sb
     if (is_partial(sx) && x->dtype != SBP_F32) return SBP_ERR_DTYPE;
     if (is_partial(sw) && w->dtype != SBP_F32) return SBP_ERR_DTYPE;
     if (x->dtype != w->dtype) {
-        if (is_partial(sx) && w->dtype == SBP_BF16) f32_operand = 1;
-        else if (is_partial(sw) && x->dtype == SBP_BF16) f32_operand = 2;
+        // fp32 next to bf16: the fp32 tensor is a P(sum) partial or the B tensor a reduced partial was boxed into
+        if (x->dtype == SBP_F32 && (is_partial(sx) || sx == SBP_B) && sw == SBP_B) f32_operand = 1;
+        else if (w->dtype == SBP_F32 && (is_partial(sw) || sw == SBP_B) && sx == SBP_B) f32_operand = 2;
         else return SBP_ERR_DTYPE;
     }
-    const int32_t want_out = is_partial(sy) ? SBP_F32 : x->dtype;
+    const int32_t want_out = (is_partial(sy) || f32_operand) ? SBP_F32 : x->dtype;
     if (y->dtype != want_out) return SBP_ERR_DTYPE;
     if (y->trans != 0) return SBP_ERR_UNSUPPORTED;
     if (epilogue != SBP_EPI_NONE && epilogue != SBP_EPI_GELU) return SBP_ERR_UNSUPPORTED;

@@ -373,6 +373,43 @@ def test_uvw_deferred_boxing_on_gpu():
         assert_matmul_close(g, ref, 1e-4, "U.V.W with one boxing at the end")
 
 
+def test_uvw_bf16_graph_box_late_equals_box_early():
+    """Sec. 3.3 with bf16 tensors: U S(1), V S(0), W B.  Deferred: (UV) stays k fp32 partials, each is
+    multiplied by W (row 4, fp32 partial x bf16), one boxing at the end.  Immediate: (UV) is boxed to
+    B first (fp32), then multiplied by W (row 6, fp32 B x bf16 B).  Both must give U V W; they differ
+    only in where the fp32 additions happen."""
+    k = 4
+    M, K1, N1, N2 = 200, 4 * 96, 264, 136
+    U, V, W = rnd_bf16(1, (M, K1)), rnd_bf16(2, (K1, N1), 0.05), rnd_bf16(3, (N1, N2), 0.05)
+    d_u = DevTensor.from_host(orc.scatter(U, orc.S1, k), M, K1, orc.S1)
+    d_v = DevTensor.from_host(orc.scatter(V, orc.S0, k), K1, N1, orc.S0)
+    d_w = DevTensor.from_host(orc.scatter(W, orc.B, k), N1, N2, orc.B)
+    uv = DevTensor.empty(M, N1, np.float32, orc.P_SUM, k)
+    sbp.sbp_matmul(d_u.desc, sbp.S(1), d_v.desc, sbp.S(0), uv.desc, sbp.AUTO, k)
+    # deferred boxing
+    uvw_p = DevTensor.empty(M, N2, np.float32, orc.P_SUM, k)
+    late = DevTensor.empty(M, N2, np.float32, orc.B, k)
+    sbp.sbp_matmul(uv.desc, sbp.P_SUM, d_w.desc, sbp.B, uvw_p.desc, sbp.AUTO, k)
+    sbp.sbp_boxing(uvw_p.desc, sbp.P_SUM, late.desc, sbp.B, k)
+    # immediate boxing
+    uv_b = DevTensor.empty(M, N1, np.float32, orc.B, k)
+    early = DevTensor.empty(M, N2, np.float32, orc.B, k)
+    sbp.sbp_boxing(uv.desc, sbp.P_SUM, uv_b.desc, sbp.B, k)
+    sbp.sbp_matmul(uv_b.desc, sbp.B, d_w.desc, sbp.B, early.desc, sbp.AUTO, k)
+    sync()
+    ref = orc.matmul(orc.matmul(values(U), values(V)), values(W))
+    for j in range(k):
+        assert_matmul_close(late.host()[j], ref, 1e-4, f"box late, copy {j}")
+        assert_matmul_close(early.host()[j], ref, 1e-4, f"box early, copy {j}")
+    # the partials of the deferred form, each against the oracle's X_i W
+    ref_uv, _ = orc.matmul_sbp([values(x) for x in orc.scatter(U, orc.S1, k)], orc.S1,
+                               [values(x) for x in orc.scatter(V, orc.S0, k)], orc.S0)
+    ref_p, sy = orc.matmul_sbp(ref_uv, orc.P_SUM, [values(W)] * k, orc.B)
+    assert sy == orc.P_SUM
+    for i, g in enumerate(uvw_p.host()):
+        assert_matmul_close(g, ref_p[i], 1e-4, f"(U_i V_i) W partial {i}")
+
+
 @pytest.mark.parametrize("k", [1, 4, 8])
 @pytest.mark.parametrize("cols", [4 * 8 * 40, 1003])
 def test_model_parallel_softmax_statistics(k, cols):
