@@ -145,6 +145,19 @@ struct Tile {
         }
     }
 
+    // The same load outside the compiler's bookkeeping (persistent kernel: every wait on the memory
+    // counter there is explicit, see its tile loop).  M0 carries the LDS address of lane 0's 16 bytes;
+    // one idle cycle separates its write from the load that reads it.
+    __device__ static void load_direct_untracked(char* lds_tile, gbl_char* src, const uint32_t (&off)[PER_THREAD], int wave) {
+#pragma unroll
+        for (int it = 0; it < PER_THREAD; ++it) {
+            const int p0 = it * NT + wave * 64;
+            const uint32_t lds = (uint32_t)(uintptr_t)(lds_void*)(lds_tile + p0 * 16);
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                         : : "v"(off[it]), "s"(src), "s"(lds) : "memory", "m0");
+        }
+    }
+
     // Fragment addressing.  The compiler tags an LDS access with the __shared__ object it touches
     // only through SHORT pointer chains, and it needs that tag to see that fragment reads of one
     // stage cannot alias direct-to-LDS loads into another (otherwise it serialises them with a
@@ -281,9 +294,36 @@ __device__ inline float mfma_epilogue(float v) {
 // Compile-time indices throughout: the accumulators must never be indexed dynamically (they would
 // move to scratch memory).  Edge tiles and result pitches that are not a multiple of 16 bytes take
 // the guarded element-wise path.
+//
+// LOADS_FIRST (persistent kernel): direct-to-LDS loads of the next tile are in flight when the
+// epilogue starts, and the caller wants to run its next two reduction steps while the stores of this
+// tile drain.  Loads and stores share one in-order completion counter, and once a store is pending
+// behind a load the compiler no longer trusts any count on it and falls back to "wait for
+// everything" at the next LDS read.  So here (a) the in-flight loads are waited for right before the
+// first store, when the first block is already staged and they are about a microsecond old, and (b)
+// the stores are issued as inline assembly, outside the compiler's bookkeeping; every later wait on
+// the counter is an explicit one that counts them in (see the tile loop of the persistent kernel).
 constexpr int STAGE_BYTES = 4096;
+constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }   // s_waitcnt vmcnt(n), nothing else
 
-template <int BM, int BN, int TM, int TN, int FM, int FN, int EPI, typename OutT>
+// 16-byte streaming store the compiler does not track.  The two idle cycles cover the hardware's
+// rule that the data registers of a store wider than 8 bytes must not be rewritten right behind it
+// (the compiler inserts them for stores it knows; here it cannot).
+template <typename V>
+__device__ inline void store16_untracked(V* p, const V v) {
+    asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+}
+// element stores of the same kind for edge tiles (a tracked store anywhere in the tile loop is enough
+// to bring the compiler's blanket waits back)
+__device__ inline void store_out_untracked(float* c, int64_t pos, float v) {
+    asm volatile("global_store_dword %0, %1, off nt" : : "v"(c + pos), "v"(v) : "memory");
+}
+__device__ inline void store_out_untracked(uint16_t* c, int64_t pos, float v) {
+    const uint32_t b = f32_to_bf16(v);
+    asm volatile("global_store_short %0, %1, off nt" : : "v"(c + pos), "v"(b) : "memory");
+}
+
+template <int BM, int BN, int TM, int TN, int FM, int FN, int EPI, typename OutT, bool LOADS_FIRST = false>
 __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&acc)[FM][FN], const GemmShard& s, int m0, int n0, int wm, int wn, int lane, char* stage) {
     OutT* C = static_cast<OutT*>(s.c);
     constexpr int EPV = 16 / (int)sizeof(OutT);   // elements per 16-byte store
@@ -312,7 +352,13 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
                 static_for<4>([&](auto qidx) {
                     constexpr int q = decltype(qidx)::value;
                     const f32x4 v = *reinterpret_cast<const f32x4*>(stage + (rd + q * 1024));
-                    __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + j * 32));
+                    f32x4* dst = reinterpret_cast<f32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + j * 32);
+                    if constexpr (LOADS_FIRST) {
+                        if constexpr (decltype(idx)::value == 0 && q == 0) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+                        store16_untracked(dst, v);
+                    } else {
+                        __builtin_nontemporal_store(v, dst);
+                    }
                 });
                 __builtin_amdgcn_wave_barrier();
             });
@@ -342,7 +388,13 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
                 static_for<4>([&](auto qidx) {
                     constexpr int q = decltype(qidx)::value;
                     const u32x4 v = *reinterpret_cast<const u32x4*>(stage + (rd + q * 1024));
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + jp * 64));
+                    u32x4* dst = reinterpret_cast<u32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + jp * 64);
+                    if constexpr (LOADS_FIRST) {
+                        if constexpr (decltype(idx)::value == 0 && q == 0) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+                        store16_untracked(dst, v);
+                    } else {
+                        __builtin_nontemporal_store(v, dst);
+                    }
                 });
                 __builtin_amdgcn_wave_barrier();
             });
@@ -359,9 +411,13 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
             constexpr int r = decltype(ridx)::value;
             const int m = mb + 8 * (r >> 2) + (r & 3);
             const float v = mfma_epilogue<EPI>(acc[i][j][r]);
-            if (m < s.m && n < s.n) store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+            if (m < s.m && n < s.n) {
+                if constexpr (LOADS_FIRST) store_out_untracked(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+                else store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+            }
         });
     });
+    if constexpr (LOADS_FIRST) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));   // edge tile: loads and stores alike
 }
 
 // Scheduling hint for one phase of NMFMA matrix instructions: let one LDS read and (for the first NVM
@@ -729,8 +785,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
     // last round; the tile loop below re-opens it there.  Past the last tile the steps are zeroed, so
     // the last stage is simply re-read (in bounds, never used).
     auto issue = [&](char* da, char* db) {
-        TA::load_direct(da, A, offa, wave);
-        TB::load_direct(db, B, offb, wave);
+        TA::load_direct_untracked(da, A, offa, wave);
+        TB::load_direct_untracked(db, B, offb, wave);
         A += stepa;
         B += stepb;
     };
@@ -757,17 +813,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
     };
     constexpr int WAIT_STRICT = (WAIT_KEEP & 15) | ((WAIT_KEEP >> 4) << 14) | 0x0070;   // vmcnt(WAIT_KEEP) lgkmcnt(0)
-    // Stores of the previous tile's epilogue sit in the same in-order queue in front of the next
-    // loads, so the first step of a tile also waits for them.
-    auto step = [&](auto cur) {
+    // Stores of a tile's epilogue sit in the in-order memory queue in front of the next tile's fourth
+    // stage.  The first two steps of a tile need stages 1 and 2 only, which the epilogue has already
+    // waited for (see store_tile), so they run on a barrier alone (NOWAIT) and the stores drain
+    // underneath them; the third step is the first to wait on the queue again, and its "all but the
+    // two youngest stages" then covers the stores as well.
+    constexpr int WAIT_LDS_ONLY = 0xC07F;   // lgkmcnt(0), vmcnt untouched
+    auto step = [&](auto cur, auto nowait) {
         constexpr int CUR = decltype(cur)::value;
+        constexpr bool NOWAIT = decltype(nowait)::value;
         using Nxt = std::integral_constant<int, (CUR + 1) % NST>;
         using Dst = std::integral_constant<int, (CUR + NST - 1) % NST>;
         issue(stA(Dst{}), stB(Dst{}));
         read_frags(stA(cur), stB(cur), 1, 1);
         mfmas(0);
         pace<FM * FN, NDS, NVM>();
-        __builtin_amdgcn_s_waitcnt(WAIT_STRICT);
+        __builtin_amdgcn_s_waitcnt(NOWAIT ? WAIT_LDS_ONLY : WAIT_STRICT);
         __builtin_amdgcn_s_barrier();
         read_frags(stA(Nxt{}), stB(Nxt{}), 0, 0);
         mfmas(1);
@@ -777,9 +838,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
     using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>;
     using I3 = std::integral_constant<int, 3>;
+    using Wait = std::false_type;
+    using NoWait = std::true_type;
+    static_assert(NST == 4, "the tile loop below is written for four stages");
 
     static_for<NST - 1>([&](auto i) { issue(stA(i), stB(i)); });
-    __builtin_amdgcn_s_waitcnt(WAIT_STRICT);
+    __builtin_amdgcn_s_waitcnt(0x0070);   // all three stages landed: the first tile starts like every other
     __builtin_amdgcn_s_barrier();
     read_frags(sA0, sB0, 0, 0);
 
@@ -795,24 +859,30 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        for (int r = 0; r < rounds; ++r) {
-            step(I0{});
-            if (r == rounds - 1) {
-                // the load cursor has issued this tile's last stage: move it to the next tile
-                if (nv < nblk) {
-                    open_tile(nv);
-                } else {
-                    A -= stepa;     // no next tile: keep re-reading the last stage
-                    B -= stepb;
-                    stepa = 0;
-                    stepb = 0;
-                }
+        // the load cursor has issued this tile's last stage: move it to the next tile
+        auto switch_tile = [&]() {
+            if (nv < nblk) {
+                open_tile(nv);
+            } else {
+                A -= stepa;     // no next tile: keep re-reading the last stage
+                B -= stepb;
+                stepa = 0;
+                stepb = 0;
             }
-            step(I1{});
-            step(I2{});
-            step(I3{});
+        };
+        step(I0{}, NoWait{});
+        if (rounds == 1) switch_tile();
+        step(I1{}, NoWait{});
+        step(I2{}, Wait{});
+        step(I3{}, Wait{});
+        for (int r = 1; r < rounds; ++r) {
+            step(I0{}, Wait{});
+            if (r == rounds - 1) switch_tile();
+            step(I1{}, Wait{});
+            step(I2{}, Wait{});
+            step(I3{}, Wait{});
         }
-        store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
+        store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT, true>(acc, s, m0, n0, wm, wn, lane, sOut);
         cv = nv;
     }
     __builtin_amdgcn_s_waitcnt(0x0070);   // trailing (unused) loads must land before LDS is released
