@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="token rows in the oracle's sample")
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
-    ap.add_argument("--tile-order", type=int, default=2, help="GEMM tile walk knob (default 2)")
+    ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
     ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw"],
                     help="mlp (default) is the workload the headline metric is quoted on")

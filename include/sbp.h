@@ -160,7 +160,8 @@ enum {
                                    (needs every local reduction length to be a multiple of 128); a
                                    forced kernel that cannot take the shapes gives SBP_ERR_UNSUPPORTED */
     SBP_KNOB_TILE_ORDER = 1     /* order in which workgroups walk output tiles: low byte = tile-rows per
-                                   band (default 2), bit 8 set = no per-XCD re-linearisation            */
+                                   band (0, the default: chosen from the shape), bit 8 set = no per-XCD
+                                   re-linearisation                                                     */
 };
 int32_t sbp_set_knob(int32_t knob, int32_t value);
 

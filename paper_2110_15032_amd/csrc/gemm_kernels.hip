@@ -217,9 +217,17 @@ __device__ inline void static_for(F&& f) {
     static_for_impl<N>(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
-// tile walk: low byte = tile-rows per band (default 2: measured 3-5 % faster than 8 on the MLP GEMMs),
-// bit 8 = skip the XCD re-linearisation
-int g_tile_order = 2;
+// tile walk: low byte = tile-rows per band (0 = chosen from the shape, see tile_order_for), bit 8 = skip
+// the XCD re-linearisation
+int g_tile_order = 0;
+
+// Band height when the knob leaves it open.  Measured with the persistent kernel (TFLOP/s at band
+// 2 / 3 / 4): 8 tile-columns per shard 1157 / 1142 / 1151; 16 columns 1049 / 1133 / 1101 and, with 4
+// tile-rows only, 960 / 998 / 1004; 489 columns 625 / 648 / 644.  So 3, except for narrow shards.
+inline int tile_order_for(int tn) {
+    if (g_tile_order & 0xFF) return g_tile_order;
+    return (g_tile_order & ~0xFF) | (tn <= 8 ? 2 : 3);
+}
 
 struct TileCoord {
     int g, tile_m, tile_n;
@@ -1065,7 +1073,7 @@ int32_t launch_split(const GemmPlan& plan, int max_m, int max_n, hipStream_t st)
     else if (plan.a_kc) kern = gemm_split_kernel<true, false, F32_B>;
     else if (plan.b_kc) kern = gemm_split_kernel<false, true, F32_B>;
     else kern = gemm_split_kernel<false, false, F32_B>;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, g_tile_order);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, tile_order_for(tn));
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }
 
@@ -1083,14 +1091,14 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
         int grid = cus / 8 * 8;
         if (grid > nblk) grid = (int)nblk;
         hipLaunchKernelGGL((gemm_mfma_persist_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 100, EPI, OutT>), dim3((uint32_t)grid),
-                           dim3(WM * WN * 64), 0, st, plan, tm, tn, g_tile_order & 0xFFFF, (int)nblk);
+                           dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
         return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
     }
     void (*kern)(GemmPlan, int, int, int);
     if constexpr (ODD >= 100) kern = nullptr;
     else if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
     else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, g_tile_order);
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn));
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
 }
 

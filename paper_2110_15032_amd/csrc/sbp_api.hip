@@ -91,7 +91,7 @@ int32_t sbp_set_knob(int32_t knob, int32_t value) {
         g_gemm_variant.store(value);
         return SBP_OK;
     }
-    if (knob == SBP_KNOB_TILE_ORDER && (value & 0xFF) >= 1 && value < 0x200) {
+    if (knob == SBP_KNOB_TILE_ORDER && value >= 0 && value < 0x200) {
         set_tile_order(value);
         return SBP_OK;
     }
