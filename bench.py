@@ -13,11 +13,12 @@ Inputs are seeded synthetic tensors, resident in HBM before the timed region.  P
 included); the per-kernel figures are in "kernels", "roofline" (dominant kernel) and
 "roofline_boxing".  The CPU oracle is timed on a bounded sample of the same workload.
 
-`--workload dp_grad | classifier | relayout | uvw` times the other full-size workloads the same way
+`--workload dp_grad | classifier | relayout | uvw | zero` times the other full-size workloads the same way
 (one JSON line each, per-kernel times in "kernels", no oracle leg): the data-parallel weight gradient
 with its reduce-scatter / all-reduce, the model-parallel classifier head with its softmax statistics,
-the pure relayout chain S(0) -> S(1) -> B -> S(0) on 16 logical devices, and Y = U V W with the boxing
-deferred to the end against boxing right after the first product.
+the pure relayout chain S(0) -> S(1) -> B -> S(0) on 16 logical devices, Y = U V W with the boxing
+deferred to the end against boxing right after the first product, and (`zero`) the two cast-fused
+boxings of a sharded optimizer state.
 """
 from __future__ import annotations
 
@@ -47,7 +48,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -435,7 +436,43 @@ def bench_uvw(args, cfg, sbp, wl, torch, np):
                        k, (f1 + f2) / (late * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
 
 
-OTHER_WORKLOADS = {"dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw}
+def bench_zero(args, cfg, sbp, wl, torch, np):
+    """Sharded optimizer state with mixed precision (Sec. 6.4), k = 8, 2^28 parameters: fp32 master
+    weights S(0) -> bf16 B (cast fused into the all-gather), and bf16 partial gradients P(sum) -> fp32
+    S(0) (cast fused into the reduce-scatter)."""
+    k = 8
+    R, C = 16384, 16384
+    arena = make_arena(torch, np, args.stagger)
+    w32 = arena([(R // k, C)] * k, torch.float32)
+    for i in range(k):
+        rows = np.arange(*wl.split_range(R, k, i))
+        w32[i].copy_(torch.from_numpy(wl.normal(wl.SEED_BASE, 200, (R, C), 0.02, rows, None, dtype=np.float32)))
+    w16 = arena([(R, C)] * k, torch.int16)
+    g16 = arena([(R, C)] * k, torch.int16)
+    for i in range(k):
+        g16[i].copy_(w16[i].random_(-30000, 30000))     # finite bf16 bit patterns (exponent field below all-ones)
+    g32 = arena([(R // k, C)] * k, torch.float32)
+    W32, W16 = sbp.SbpTensor(w32, R, C, sbp.F32), sbp.SbpTensor(w16, R, C, sbp.BF16)
+    G16, G32 = sbp.SbpTensor(g16, R, C, sbp.BF16), sbp.SbpTensor(g32, R, C, sbp.F32)
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_boxing_cast(W32, sbp.S(0), W16, sbp.B, k, st),
+                lambda st: sbp.sbp_boxing_cast(G16, sbp.P_SUM, G32, sbp.S(0), k, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    n = float(R) * C
+    by = [4 * n + 2 * n * k, 2 * n * k + 4 * n]
+    g = [by[i] / ms[i] / 1e6 for i in range(2)]
+    kernels = {"cast_all_gather_ms": round(ms[0], 4), "cast_all_gather_gbps": round(g[0], 1),
+               "cast_reduce_scatter_ms": round(ms[1], 4), "cast_reduce_scatter_gbps": round(g[1], 1)}
+    roof = {"bound": "hbm", "kernel": "sbp_boxing_cast fp32 S(0) -> bf16 B (1 GiB read, 4 GiB written)", "achieved": round(g[0], 1),
+            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g[0] / PEAK_HBM_GBPS, 4), "traffic": None}
+    return result_line(args, "sharded optimizer state, k=8, 2^28 parameters: fp32 S(0) -> bf16 B and bf16 P(sum) -> fp32 S(0)",
+                       k, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
+
+
+OTHER_WORKLOADS = {"dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
+                   "zero": bench_zero}
 
 
 def cpu_baseline(cfg, k, rows, seed):

@@ -138,6 +138,17 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w,
 int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out, sbp_t sbp_out,
                    int32_t k, void* stream);
 
+/* Precision cast fused into boxing (Sec. 6.4, sharded optimizer state with mixed
+ * precision: the cast op's input is S(0) and its output B).
+ *   forward:   in SBP_F32  S(a)    -> out SBP_BF16 B     out_j = bf16(concat_i in_i), every j;
+ *              one rounding to nearest even (cast + all-gather in one pass)
+ *   backward:  in SBP_BF16 P(sum)  -> out SBP_F32  S(a)  out_j = sum_i f32(in_i)[slice_j];
+ *              widened exactly, added in fp32 in shard order (cast + reduce-scatter)
+ * Same shape, ownership and alias rules as sbp_boxing.  Any other pair of signatures
+ * is SBP_ERR_SIGNATURE, any other pair of dtypes SBP_ERR_DTYPE. */
+int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out, sbp_t sbp_out,
+                        int32_t k, void* stream);
+
 /* Local reductions of the model-parallel softmax (Sec. 6.3.1): logits [R, C] are
  * S(1); each device reduces the columns it holds.
  *   sbp_row_max:    m_i[r] = max_c L_i[r, c]              -> out [R,1] f32, P(max)

@@ -27,7 +27,7 @@ KNOB_GEMM_VARIANT = 0
 KNOB_TILE_ORDER = 1
 
 #: every symbol include/sbp.h declares
-EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing",
+EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing", "sbp_boxing_cast",
            "sbp_row_max", "sbp_row_sumexp", "sbp_set_knob", "sbp_strerror")
 
 
@@ -64,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.sbp_matmul.argtypes = [T, i32, T, i32, T, i32, i32, vp]
         L.sbp_matmul_ex.argtypes = [T, i32, T, i32, T, i32, i32, vp, i32]
         L.sbp_boxing.argtypes = [T, i32, T, i32, i32, vp]
+        L.sbp_boxing_cast.argtypes = [T, i32, T, i32, i32, vp]
         L.sbp_row_max.argtypes = [T, i32, T, i32, vp]
         L.sbp_row_sumexp.argtypes = [T, i32, T, T, i32, vp]
         L.sbp_set_knob.argtypes = [i32, i32]
@@ -135,6 +136,10 @@ def sbp_matmul_ex(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTens
 
 def sbp_boxing(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
     _check(lib().sbp_boxing(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing")
+
+
+def sbp_boxing_cast(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
+    _check(lib().sbp_boxing_cast(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing_cast")
 
 
 def sbp_row_max(logits: SbpTensor, sbp_l: int, out: SbpTensor, k: int, stream=None) -> None:

@@ -290,6 +290,101 @@ __global__ __launch_bounds__(BOX_THREADS) void box_gather_bcast_kernel(BoxParams
         if (pos[u] < total) __builtin_nontemporal_store(val[u], dst + pos[u]);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Cast fused into boxing (Sec. 6.4: sharded optimizer state with mixed precision).
+// Forward, fp32 S(a) -> bf16 B: the walk of box_gather_bcast_kernel (chunked passes, one destination at
+// a time, re-reads from L2) with VE elements per lane: 32 bytes in, one hardware conversion per pair
+// (round to nearest even), 16 bytes out.  VE = 1 is the fallback for shapes without 8-element alignment.
+// ------------------------------------------------------------------------------------------------
+__device__ inline uint32_t cvt2_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+template <int VE>
+__global__ __launch_bounds__(BOX_THREADS) void box_cast_gather_kernel(BoxParams p, uint32_t log2_pieces, uint32_t total,
+                                                                       uint32_t q, uint32_t rem) {
+    __shared__ const float* sp[SBP_MAX_K];
+    if ((int)threadIdx.x < p.k) sp[threadIdx.x] = static_cast<const float*>(p.src[threadIdx.x]);
+    __syncthreads();
+    const uint32_t k = (uint32_t)p.k;
+    const uint32_t piece = blockIdx.x & ((1u << log2_pieces) - 1);
+    const uint32_t cj = blockIdx.x >> log2_pieces;
+    const uint32_t chunk = cj / k, j = cj - chunk * k;
+    const uint32_t idx = ((chunk << log2_pieces) + piece) * (uint32_t)BOX_THREADS + threadIdx.x;   // group of VE elements
+    if (idx >= total) return;
+    const uint32_t cols_v = (uint32_t)(p.cols / VE);
+    const uint32_t r = idx / cols_v, c = idx - r * cols_v;
+    const bool by_rows = p.axis_in == 0;
+    const uint32_t x = by_rows ? r : c * VE;
+    const uint32_t edge = rem * (q + 1);
+    uint32_t i, begin, len;
+    if (x < edge) {
+        i = x / (q + 1);
+        begin = i * (q + 1);
+        len = q + 1;
+    } else {
+        i = (x - edge) / (q ? q : 1);
+        begin = edge + i * q;
+        i += rem;
+        len = q;
+    }
+    const int64_t spos = by_rows ? ((int64_t)(r - begin) * p.cols + (int64_t)c * VE) : ((int64_t)r * len + (x - begin));   // elements
+    const float* src = sp[i] + spos;
+    if constexpr (VE == 8) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
+        const u32x4 o = {cvt2_bf16(a[0], a[1]), cvt2_bf16(a[2], a[3]), cvt2_bf16(b[0], b[1]), cvt2_bf16(b[2], b[3])};
+        __builtin_nontemporal_store(o, static_cast<u32x4*>(p.dst[j]) + idx);
+    } else {
+        static_cast<uint16_t*>(p.dst[j])[idx] = (uint16_t)(cvt2_bf16(*src, 0.0f) & 0xFFFFu);
+    }
+}
+
+// Backward, bf16 P(sum) -> fp32 S(a): out_j = sum over the k partials of slice j, widened to fp32 and
+// added in shard order.  Tasks as for P -> S (one per destination).
+template <int VE, int KS>
+__global__ __launch_bounds__(BOX_THREADS) void box_cast_reduce_kernel(BoxParams p) {
+    const Task T = make_task(p, blockIdx.y);
+    const int32_t ns = KS > 0 ? KS : T.ns;
+    const uint32_t cols_v = (uint32_t)(T.cols / VE);
+    const uint32_t total = (uint32_t)T.rows * cols_v;
+    const uint32_t stride = gridDim.x * BOX_THREADS;
+    float* __restrict__ dst = static_cast<float*>(p.dst[T.d0]);
+    for (uint32_t idx = blockIdx.x * BOX_THREADS + threadIdx.x; idx < total; idx += stride) {
+        const uint32_t r = T.rows == 1 ? 0 : idx / cols_v;
+        const uint32_t c = idx - r * cols_v;
+        const int64_t spos = T.src_off + (int64_t)r * T.src_ld + (int64_t)c * VE;
+        const int64_t dpos = T.dst_off + (int64_t)r * T.dst_ld + (int64_t)c * VE;
+        if constexpr (VE == 8) {
+            float acc[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+            auto add = [&](int i) {
+                const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.src[i]) + spos));
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    acc[2 * d] += __uint_as_float(w[d] << 16);
+                    acc[2 * d + 1] += __uint_as_float(w[d] & 0xFFFF0000u);
+                }
+            };
+            if constexpr (KS > 0) {
+#pragma unroll
+                for (int i = 0; i < KS; ++i) add(i);
+            } else {
+                for (int i = 0; i < ns; ++i) add(i);
+            }
+            const f32x4 o0 = {acc[0], acc[1], acc[2], acc[3]}, o1 = {acc[4], acc[5], acc[6], acc[7]};
+            __builtin_nontemporal_store(o0, reinterpret_cast<f32x4*>(dst + dpos));
+            __builtin_nontemporal_store(o1, reinterpret_cast<f32x4*>(dst + dpos + 4));
+        } else {
+            float acc = 0.0f;
+            for (int i = 0; i < ns; ++i) acc += __uint_as_float((uint32_t)static_cast<const uint16_t*>(p.src[i])[spos] << 16);
+            dst[dpos] = acc;
+        }
+    }
+}
+
 // S(a) -> P(op), B -> P(op) (Table 2 prices them at zero on the same devices): device j keeps what it
 // already holds, placed in the full-shape partial, and every other position gets the identity of
 // the reduction (0 / -inf).  B: device 0 keeps its copy, the others hold the identity only.
@@ -480,6 +575,77 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
         else launch_copy<uint16_t>(p, grid, 4, stream);
     }
     return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+}
+
+int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream) {
+    BoxParams p{};
+    p.rows = plan.rows;
+    p.cols = plan.cols;
+    p.k = plan.k;
+    p.axis_in = (plan.sbp_in == SBP_S(0) || plan.sbp_in == SBP_S(1)) ? plan.sbp_in : -1;
+    p.axis_out = (plan.sbp_out == SBP_S(0) || plan.sbp_out == SBP_S(1)) ? plan.sbp_out : -1;
+    for (int i = 0; i < plan.k; ++i) {
+        p.src[i] = plan.src[i];
+        p.dst[i] = plan.dst[i];
+    }
+    if (plan.rows * plan.cols == 0) return SBP_OK;
+    if (plan.rows >= ((int64_t)1 << 31) || plan.cols >= ((int64_t)1 << 31)) return SBP_ERR_UNSUPPORTED;
+    if (p.axis_in >= 0 && plan.sbp_out == SBP_B) {
+        // forward: fp32 S(a) -> bf16 B.  8 elements per lane when rows and shard boundaries allow it.
+        int64_t g = gcd64(8, plan.cols);
+        if (p.axis_in == 1)
+            for (int32_t i = 0; i < plan.k; ++i) {
+                g = gcd64(g, split_begin(plan.cols, plan.k, i));
+                g = gcd64(g, split_len(plan.cols, plan.k, i));
+            }
+        const int ve = g == 8 ? 8 : 1;
+        const int64_t total = plan.rows * plan.cols / ve;
+        if (total >= ((int64_t)1 << 31)) return SBP_ERR_UNSUPPORTED;
+        const int64_t need = (total + BOX_THREADS - 1) / BOX_THREADS;
+        uint32_t lp = 3;
+        while (lp < 11 && ((int64_t)1 << lp) < need) ++lp;
+        const int64_t chunks = (need + ((int64_t)1 << lp) - 1) >> lp;
+        const int64_t blocks = (chunks * plan.k) << lp;
+        if (blocks >= ((int64_t)1 << 31)) return SBP_ERR_UNSUPPORTED;
+        const int64_t n = p.axis_in == 0 ? plan.rows : plan.cols;
+        const uint32_t q = (uint32_t)(n / plan.k), rem = (uint32_t)(n % plan.k);
+        if (ve == 8)
+            hipLaunchKernelGGL(box_cast_gather_kernel<8>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp, (uint32_t)total, q, rem);
+        else
+            hipLaunchKernelGGL(box_cast_gather_kernel<1>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp, (uint32_t)total, q, rem);
+        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    }
+    if (plan.sbp_in == SBP_P_SUM && p.axis_out >= 0) {
+        // backward: bf16 P(sum) -> fp32 S(a)
+        p.mode = M_P2S;
+        p.vec_elems = 1;
+        int64_t g = 8, max_units = 0;
+        for (int32_t t = 0; t < plan.k; ++t) {
+            const Task T = make_task(p, t);
+            if (T.rows * T.cols == 0) continue;
+            g = gcd64(g, T.cols);
+            g = gcd64(g, T.src_off);
+            g = gcd64(g, T.dst_off);
+            if (T.rows > 1) {
+                g = gcd64(g, T.src_ld);
+                g = gcd64(g, T.dst_ld);
+            }
+            max_units = T.rows * T.cols > max_units ? T.rows * T.cols : max_units;
+        }
+        if (max_units == 0) return SBP_OK;
+        const int ve = g == 8 ? 8 : 1;
+        max_units /= ve;
+        if (max_units >= ((int64_t)1 << 31)) return SBP_ERR_UNSUPPORTED;
+        int64_t bx = (max_units + BOX_THREADS - 1) / BOX_THREADS;
+        const int64_t cap = (65536 + plan.k - 1) / plan.k;
+        if (bx > cap) bx = cap;
+        const dim3 grid((uint32_t)bx, (uint32_t)plan.k);
+        if (ve == 8 && plan.k == 8) hipLaunchKernelGGL((box_cast_reduce_kernel<8, 8>), grid, dim3(BOX_THREADS), 0, stream, p);
+        else if (ve == 8) hipLaunchKernelGGL((box_cast_reduce_kernel<8, 0>), grid, dim3(BOX_THREADS), 0, stream, p);
+        else hipLaunchKernelGGL((box_cast_reduce_kernel<1, 0>), grid, dim3(BOX_THREADS), 0, stream, p);
+        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    }
+    return SBP_ERR_UNSUPPORTED;
 }
 
 }  // namespace sbp

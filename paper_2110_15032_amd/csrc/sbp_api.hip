@@ -225,6 +225,40 @@ int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, 
     return launch_boxing(plan, static_cast<hipStream_t>(stream));
 }
 
+int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
+                        void* stream) {
+    if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
+    if (!in || !out) return SBP_ERR_NULL;
+    int32_t st;
+    if ((st = check_tensor(in, s_in, k)) != SBP_OK) return st;
+    if ((st = check_tensor(out, s_out, k)) != SBP_OK) return st;
+    if (in->rows != out->rows || in->cols != out->cols) return SBP_ERR_SHAPE;
+    if (in->trans || out->trans) return SBP_ERR_UNSUPPORTED;
+    const bool s_src = s_in == SBP_S(0) || s_in == SBP_S(1), s_dst = s_out == SBP_S(0) || s_out == SBP_S(1);
+    const bool forward = s_src && s_out == SBP_B, backward = s_in == SBP_P_SUM && s_dst;
+    if (!forward && !backward) return SBP_ERR_SIGNATURE;
+    if (forward && (in->dtype != SBP_F32 || out->dtype != SBP_BF16)) return SBP_ERR_DTYPE;
+    if (backward && (in->dtype != SBP_BF16 || out->dtype != SBP_F32)) return SBP_ERR_DTYPE;
+
+    std::vector<Span> ins, outs;
+    spans_of(in, s_in, k, ins);
+    spans_of(out, s_out, k, outs);
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    BoxPlan plan{};
+    plan.rows = in->rows;
+    plan.cols = in->cols;
+    plan.k = k;
+    plan.sbp_in = s_in;
+    plan.sbp_out = s_out;
+    plan.elem_bytes = 0;
+    for (int32_t i = 0; i < k; ++i) {
+        plan.src[i] = in->shard[i];
+        plan.dst[i] = out->shard[i];
+    }
+    return launch_boxing_cast(plan, static_cast<hipStream_t>(stream));
+}
+
 static int32_t row_stat(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* gmax, const sbp_tensor_t* out,
                         int32_t k, void* stream, bool sumexp) {
     if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;

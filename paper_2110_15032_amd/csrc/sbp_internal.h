@@ -36,6 +36,8 @@ struct BoxPlan {
 };
 
 int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream);
+// fp32 S(a) -> bf16 B (cast + all-gather) and bf16 P(sum) -> fp32 S(a) (cast + reduce-scatter); elem_bytes unused
+int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
 // Grouped GEMM: shard g computes C_g[m, n] = sum_kk A_g[m, kk] * B_g[kk, n].

@@ -113,6 +113,47 @@ def test_boxing_into_partial_keeps_values_in_place(k, op, si):
         assert np.array_equal(orc.assemble([g.astype(np.float64) for g in got], so), T.astype(np.float64))
 
 
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_cast_fused_into_all_gather(k, axis):
+    """Sec. 6.4 forward: fp32 S(a) -> bf16 B, one rounding to nearest even.  Bit-exact against the
+    oracle's rounding of the assembled tensor; ties, values that round up into the next binade,
+    subnormals and infinities planted."""
+    si = orc.S0 if axis == 0 else orc.S1
+    for n, shape in enumerate(SHAPES + [(256, 1032), (96, 8 * 16 * 5)]):
+        T = rnd_f32(500 + n, shape)
+        flat = T.reshape(-1)
+        special = np.array([1.00390625, 1.01171875, -1.00390625, 3.3895313892515355e38, 1e-40, -0.0, np.inf, 255.5], np.float32)
+        flat[: min(special.size, flat.size)] = special[: flat.size]
+        ins = orc.scatter(T, si, k)
+        d_in = DevTensor.from_host(ins, *shape, si)
+        d_out = DevTensor.empty(*shape, np.uint16, orc.B, k)
+        sbp.sbp_boxing_cast(d_in.desc, TO_ABI[si], d_out.desc, sbp.B, k)
+        sync()
+        ref = orc.bf16_round(T.astype(np.float64))
+        for j, g in enumerate(d_out.host()):
+            assert_bits_equal(g, ref, f"cast + all-gather S({axis})->B k={k} shape={shape} copy {j}")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 5])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_cast_fused_into_reduce_scatter(k, axis):
+    """Sec. 6.4 backward: k bf16 partial gradients -> fp32 S(a): widened exactly, summed in fp32."""
+    so = orc.S0 if axis == 0 else orc.S1
+    for n, shape in enumerate(SHAPES + [(256, 1032), (96, 8 * 16 * 5)]):
+        parts = [rnd_bf16(600 + 20 * n + i, shape) for i in range(k)]
+        vals = [values(p) for p in parts]
+        ref = orc.boxing(vals, orc.P_SUM, so, k)
+        d_in = DevTensor.from_host(parts, *shape, orc.P_SUM)
+        d_out = DevTensor.empty(*shape, np.float32, so, k)
+        sbp.sbp_boxing_cast(d_in.desc, sbp.P_SUM, d_out.desc, TO_ABI[so], k)
+        sync()
+        for j, g in enumerate(d_out.host()):
+            sl = [orc.scatter(v, so, k)[j] for v in vals]
+            assert g.shape == ref[j].shape
+            assert_psum_close(g, sl, ref[j], f"cast + reduce-scatter P->S({axis}) k={k} shape={shape} shard {j}")
+
+
 def test_boxing_is_reproducible_run_to_run():
     k, shape = 8, (512, 640)
     parts = [rnd_f32(300 + i, shape) for i in range(k)]
@@ -241,6 +282,20 @@ def test_matmul_partial_fp32_times_bf16(row, tx, tw, shape):
     for i in range(k):
         assert got[i].dtype == np.float32 and got[i].shape == ref[i].shape
         assert_matmul_close(got[i], ref[i], 1e-5, f"row {row} trans=({tx},{tw}) shape={shape} partial {i}")
+
+
+def test_matmul_bf16_persistent_kernel_uneven_shards():
+    """S(0) x B with M = 5 * 256 + 3 over k = 5: three shards of 257 rows (two tile-rows, the second
+    one row high), two of 256 (one tile-row), so the tile list has holes the persistent walk must
+    skip; and k = 8 over 1100 rows with a 1024-deep reduction, eight rounds per tile."""
+    for k, M, K, N in [(5, 1283, 256, 1304), (8, 1100, 1024, 520)]:
+        X, W = rnd_bf16(5, (M, K)), rnd_bf16(6, (K, N), 0.05)
+        Xs, Ws = orc.scatter(X, orc.S0, k), orc.scatter(W, orc.B, k)
+        ref, sy = orc.matmul_sbp([values(x) for x in Xs], orc.S0, [values(w) for w in Ws], orc.B)
+        got, _ = run_matmul(Xs, orc.S0, Ws, orc.B, M, K, N, k, variant=12)
+        for i in range(k):
+            assert got[i].shape == ref[i].shape
+            assert_matmul_close(values(got[i]), ref[i], 2e-2, f"uneven S(0) shards, k={k}, shard {i}")
 
 
 def test_matmul_bf16_odd_shapes_fall_back():

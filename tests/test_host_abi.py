@@ -129,6 +129,22 @@ def test_boxing_validation_errors():
     assert status_of(sbp.sbp_boxing, same, sbp.B, same, sbp.S(0), k, st) == -7         # ...but not as its own output
 
 
+def test_boxing_cast_validation_errors():
+    k = 2
+    f32_in, bf_out = fake(k, 8, 16), fake(k, 8, 16, sbp.BF16, base=0x20000000)
+    bf_in, f32_out = fake(k, 8, 16, sbp.BF16), fake(k, 8, 16, base=0x20000000)
+    st = 0
+    assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.S(0), f32_out, sbp.B, k, st) == -4       # forward writes bf16
+    assert status_of(sbp.sbp_boxing_cast, bf_in, sbp.S(0), bf_out, sbp.B, k, st) == -4         # forward reads fp32
+    assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.P_SUM, f32_out, sbp.S(0), k, st) == -4   # backward reads bf16
+    assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.B, bf_out, sbp.S(0), k, st) == -6        # not a cast pattern
+    assert status_of(sbp.sbp_boxing_cast, bf_in, sbp.P_MAX, f32_out, sbp.S(0), k, st) == -6
+    assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.S(0), fake(k, 8, 8, sbp.BF16, base=0x20000000), sbp.B, k, st) == -3
+    assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.S(0), bf_out, sbp.B, 0, st) == -2
+    over = fake(k, 8, 16, sbp.BF16, base=0x10000000)
+    assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.S(0), over, sbp.B, k, st) == -7          # output over the input
+
+
 def test_row_stat_validation_errors():
     k = 4
     L = fake(k, 16, 64, sbp.BF16)
