@@ -18,7 +18,9 @@ Signatures are spelled here as tuples: ("S", 0), ("S", 1), ("B",),
 Pins (tests/test_oracle_*.py): Table 1 derived by brute force, the reassembly
 invariant under every boxing, Table 2's closed forms, numpy float64 matmul on
 the k = 1 case, torch's fp32->bf16 cast, the Table 4 program and the U.V.W
-deferred-boxing example.  Parity unpinned by the paper (fixed by a stated
+deferred-boxing example; for the two-dimensional signatures of Sec. 3.3, Table 3
+as printed plus a brute-force derivation of every valid 2-D MatMul pair, and
+the reassembly invariant of boxing along either grid axis.  Parity unpinned by the paper (fixed by a stated
 reading only): the uneven-split rule, the GeLU variant, and which sign a
 P(max) of +0 and -0 yields.
 """
@@ -203,6 +205,75 @@ def matmul_sbp(Xs: list[np.ndarray], sbp_x, Ws: list[np.ndarray], sbp_w):
         raise ValueError(f"({sbp_x}, {sbp_w}) is not a valid MatMul signature")
     assert len(Xs) == len(Ws)
     return [matmul(x, w) for x, w in zip(Xs, Ws)], sbp_y
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.3: two-dimensional SBP (Table 3)
+# ----------------------------------------------------------------------------
+# The logical devices form a k0 x k1 grid (k0 nodes of k1 devices).  A signature is a pair
+# (outer, inner): `outer` maps the global tensor onto the k0 nodes, `inner` maps each node's
+# tensor onto that node's k1 devices.  Device (a, b) is entry a * k1 + b of every list below.
+def local_shape2(rows: int, cols: int, sbp2, k0: int, k1: int, a: int, b: int) -> tuple[int, int]:
+    r, c = local_shape(rows, cols, sbp2[0], k0, a)
+    return local_shape(r, c, sbp2[1], k1, b)
+
+
+def scatter2(T: np.ndarray, sbp2, k0: int, k1: int) -> list[np.ndarray]:
+    """Global tensor -> k0 * k1 local tensors: scatter over the nodes, then each
+    node's tensor over its devices."""
+    out = []
+    for node in scatter(T, sbp2[0], k0):
+        out.extend(scatter(node, sbp2[1], k1))
+    return out
+
+
+def assemble2(shards: list[np.ndarray], sbp2, k0: int, k1: int) -> np.ndarray:
+    """The inverse: every node's tensor from its k1 devices, then the global one."""
+    assert len(shards) == k0 * k1
+    nodes = [assemble(shards[a * k1:(a + 1) * k1], sbp2[1]) for a in range(k0)]
+    return assemble(nodes, sbp2[0])
+
+
+def infer_matmul2(sbp_x2, sbp_w2):
+    """Table 1 applied to each grid axis on its own (the two rows printed in
+    Table 3 are two instances); None when either axis is not a Table 1 row."""
+    y0, y1 = infer_matmul(sbp_x2[0], sbp_w2[0]), infer_matmul(sbp_x2[1], sbp_w2[1])
+    return None if y0 is None or y1 is None else (y0, y1)
+
+
+def matmul_sbp2(Xs: list[np.ndarray], sbp_x2, Ws: list[np.ndarray], sbp_w2):
+    """Every device multiplies the two local tensors it holds."""
+    sbp_y2 = infer_matmul2(sbp_x2, sbp_w2)
+    if sbp_y2 is None:
+        raise ValueError(f"({sbp_x2}, {sbp_w2}) is not a valid 2-D MatMul signature")
+    assert len(Xs) == len(Ws)
+    return [matmul(x, w) for x, w in zip(Xs, Ws)], sbp_y2
+
+
+def boxing2(shards: list[np.ndarray], sbp_in2, sbp_out2, k0: int, k1: int) -> list[np.ndarray]:
+    """Boxing along ONE grid axis (the other position of the signature stays).
+    Inner position: each node re-arranges its own tensor (1-D boxing per node).
+    Outer position: the devices with the same inner index b hold, between
+    them, one tensor under the outer signature (the whole tensor when inner is
+    B or P, its b-th slice when inner is S and the outer conversion leaves that
+    axis alone); each such group is boxed on its own."""
+    assert len(shards) == k0 * k1
+    if sbp_in2[0] == sbp_out2[0]:
+        out = []
+        for a in range(k0):
+            out.extend(boxing(shards[a * k1:(a + 1) * k1], sbp_in2[1], sbp_out2[1], k1))
+        return out
+    if sbp_in2[1] != sbp_out2[1]:
+        raise ValueError("boxing2 changes one position of the signature at a time")
+    inner = sbp_in2[1]
+    if inner in (S0, S1) and inner in (sbp_in2[0], sbp_out2[0]):
+        raise ValueError("outer boxing along the axis the inner position splits is not a per-slice operation")
+    out = [None] * (k0 * k1)
+    for b in range(k1):
+        plane = boxing([shards[a * k1 + b] for a in range(k0)], sbp_in2[0], sbp_out2[0], k0)
+        for a in range(k0):
+            out[a * k1 + b] = plane[a]
+    return out
 
 
 # ----------------------------------------------------------------------------
