@@ -149,6 +149,30 @@ int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out
 int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out, sbp_t sbp_out,
                         int32_t k, void* stream);
 
+/* Two-dimensional SBP (Sec. 3.3, Table 3).  The logical devices form a k0 x k1 grid (k0 groups
+ * of k1 devices, k0 * k1 <= SBP_MAX_K); a signature is a pair s[2] = (outer, inner): the outer
+ * entry places the tensor on the k0 groups, the inner entry places each group's tensor on its
+ * k1 devices (balanced splits, nested).  Device (a, b) is shard[a * k1 + b].  trans must be 0.
+ *
+ * sbp_infer_matmul_2d: Table 1 applied to each grid axis on its own; Table 3's two rows,
+ *   ((S0,B),(B,S1)) -> (S0,S1) and ((S0,S1),(B,S0)) -> (S0,P(sum)), are two instances.
+ * sbp_matmul_2d: every device multiplies the two local tensors it holds (one grouped launch).
+ *   sbp_y may be NULL or hold SBP_AUTO entries; otherwise it must equal the deduced pair.
+ *   dtype rules as for sbp_matmul (a tensor with P(sum) in either position is SBP_F32).
+ * sbp_boxing_2d: boxing along ONE grid axis; the other entry of the signature must stay.
+ *   Inner entry changes: every group re-arranges its own tensor.  Outer entry changes: the
+ *   devices with equal inner index b are boxed among themselves (they hold the whole tensor
+ *   when the inner entry is B or P, slice b of it when the inner entry is S(d) and neither outer
+ *   entry is S(d); an outer conversion along the inner split's own axis is SBP_ERR_UNSUPPORTED,
+ *   as is changing both entries in one call).  Every part is validated before any is enqueued. */
+int32_t sbp_infer_matmul_2d(const sbp_t* sbp_x, const sbp_t* sbp_w, sbp_t* sbp_y);
+int32_t sbp_local_shape_2d(int64_t rows, int64_t cols, const sbp_t* sbp, int32_t k0, int32_t k1,
+                           int32_t a, int32_t b, int64_t* local_rows, int64_t* local_cols);
+int32_t sbp_matmul_2d(const sbp_tensor_t* x, const sbp_t* sbp_x, const sbp_tensor_t* w, const sbp_t* sbp_w,
+                      const sbp_tensor_t* y, const sbp_t* sbp_y, int32_t k0, int32_t k1, void* stream);
+int32_t sbp_boxing_2d(const sbp_tensor_t* in, const sbp_t* sbp_in, const sbp_tensor_t* out, const sbp_t* sbp_out,
+                      int32_t k0, int32_t k1, void* stream);
+
 /* Local reductions of the model-parallel softmax (Sec. 6.3.1): logits [R, C] are
  * S(1); each device reduces the columns it holds.
  *   sbp_row_max:    m_i[r] = max_c L_i[r, c]              -> out [R,1] f32, P(max)

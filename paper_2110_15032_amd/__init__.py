@@ -9,5 +9,6 @@ from .binding import (  # noqa: F401
     S, B, P_SUM, P_MAX, AUTO, F32, BF16, EPI_NONE, EPI_GELU, KNOB_GEMM_VARIANT, KNOB_TILE_ORDER,
     SbpError, SbpTensor, lib, lib_path,
     sbp_infer_matmul, sbp_local_shape, sbp_matmul, sbp_matmul_ex, sbp_boxing, sbp_boxing_cast,
+    sbp_infer_matmul_2d, sbp_local_shape_2d, sbp_matmul_2d, sbp_boxing_2d,
     sbp_row_max, sbp_row_sumexp, sbp_set_knob, sbp_strerror, EXPORTS,
 )

@@ -28,6 +28,7 @@ KNOB_TILE_ORDER = 1
 
 #: every symbol include/sbp.h declares
 EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing", "sbp_boxing_cast",
+           "sbp_infer_matmul_2d", "sbp_local_shape_2d", "sbp_matmul_2d", "sbp_boxing_2d",
            "sbp_row_max", "sbp_row_sumexp", "sbp_set_knob", "sbp_strerror")
 
 
@@ -56,6 +57,14 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2110_15032_amd.build`")
+        # PyTorch ships its own copy of the HIP runtime.  Callers hand this library device memory and
+        # streams that PyTorch owns, so both must sit on ONE runtime: let PyTorch's load first (the
+        # library's dependency then resolves to it); loaded the other way round, this library's
+        # launches go to a second runtime that does not know the device PyTorch has opened.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(_LIB_PATH)
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
         T = ctypes.POINTER(_CTensor)
@@ -65,6 +74,11 @@ def lib() -> ctypes.CDLL:
         L.sbp_matmul_ex.argtypes = [T, i32, T, i32, T, i32, i32, vp, i32]
         L.sbp_boxing.argtypes = [T, i32, T, i32, i32, vp]
         L.sbp_boxing_cast.argtypes = [T, i32, T, i32, i32, vp]
+        P2 = ctypes.POINTER(i32)
+        L.sbp_infer_matmul_2d.argtypes = [P2, P2, P2]
+        L.sbp_local_shape_2d.argtypes = [i64, i64, P2, i32, i32, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.sbp_matmul_2d.argtypes = [T, P2, T, P2, T, P2, i32, i32, vp]
+        L.sbp_boxing_2d.argtypes = [T, P2, T, P2, i32, i32, vp]
         L.sbp_row_max.argtypes = [T, i32, T, i32, vp]
         L.sbp_row_sumexp.argtypes = [T, i32, T, T, i32, vp]
         L.sbp_set_knob.argtypes = [i32, i32]
@@ -140,6 +154,34 @@ def sbp_boxing(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int
 
 def sbp_boxing_cast(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
     _check(lib().sbp_boxing_cast(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing_cast")
+
+
+def _pair(s):
+    return (ctypes.c_int32 * 2)(int(s[0]), int(s[1]))
+
+
+def sbp_infer_matmul_2d(sbp_x, sbp_w):
+    y = (ctypes.c_int32 * 2)()
+    _check(lib().sbp_infer_matmul_2d(_pair(sbp_x), _pair(sbp_w), y), "sbp_infer_matmul_2d")
+    return (y[0], y[1])
+
+
+def sbp_local_shape_2d(rows: int, cols: int, sbp2, k0: int, k1: int, a: int, b: int):
+    lr, lc = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().sbp_local_shape_2d(rows, cols, _pair(sbp2), k0, k1, a, b, ctypes.byref(lr), ctypes.byref(lc)),
+           "sbp_local_shape_2d")
+    return lr.value, lc.value
+
+
+def sbp_matmul_2d(x: SbpTensor, sbp_x, w: SbpTensor, sbp_w, y: SbpTensor, sbp_y, k0: int, k1: int, stream=None) -> None:
+    sy = _pair(sbp_y) if sbp_y is not None else None
+    _check(lib().sbp_matmul_2d(x.ref(), _pair(sbp_x), w.ref(), _pair(sbp_w), y.ref(), sy, k0, k1, _stream_ptr(stream)),
+           "sbp_matmul_2d")
+
+
+def sbp_boxing_2d(inp: SbpTensor, sbp_in, out: SbpTensor, sbp_out, k0: int, k1: int, stream=None) -> None:
+    _check(lib().sbp_boxing_2d(inp.ref(), _pair(sbp_in), out.ref(), _pair(sbp_out), k0, k1, _stream_ptr(stream)),
+           "sbp_boxing_2d")
 
 
 def sbp_row_max(logits: SbpTensor, sbp_l: int, out: SbpTensor, k: int, stream=None) -> None:

@@ -498,7 +498,7 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
         if (g == 4) launch_to_partial<f32x4>(p, maxop, grid, (uint32_t)total_v, stream);
         else if (g == 2) launch_to_partial<f32x2>(p, maxop, grid, (uint32_t)total_v, stream);
         else launch_to_partial<float>(p, maxop, grid, (uint32_t)total_v, stream);
-        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        return launch_status(__func__);
     } else if (p_in && plan.sbp_out == SBP_B) {
         p.mode = M_P2B;
         tasks = 1;
@@ -553,7 +553,7 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
             const int64_t n = p.axis_in == 0 ? plan.rows : plan.cols;
             hipLaunchKernelGGL(box_gather_bcast_kernel<u32x4>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp,
                                (uint32_t)total_v, (uint32_t)(n / plan.k), (uint32_t)(n % plan.k));
-            return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+            return launch_status(__func__);
         }
     }
     int unroll = 1;
@@ -574,7 +574,7 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
         else if (vb == 4) launch_copy<uint32_t>(p, grid, 4, stream);
         else launch_copy<uint16_t>(p, grid, 4, stream);
     }
-    return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    return launch_status(__func__);
 }
 
 int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream) {
@@ -613,7 +613,7 @@ int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream) {
             hipLaunchKernelGGL(box_cast_gather_kernel<8>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp, (uint32_t)total, q, rem);
         else
             hipLaunchKernelGGL(box_cast_gather_kernel<1>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp, (uint32_t)total, q, rem);
-        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        return launch_status(__func__);
     }
     if (plan.sbp_in == SBP_P_SUM && p.axis_out >= 0) {
         // backward: bf16 P(sum) -> fp32 S(a)
@@ -643,7 +643,7 @@ int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream) {
         if (ve == 8 && plan.k == 8) hipLaunchKernelGGL((box_cast_reduce_kernel<8, 8>), grid, dim3(BOX_THREADS), 0, stream, p);
         else if (ve == 8) hipLaunchKernelGGL((box_cast_reduce_kernel<8, 0>), grid, dim3(BOX_THREADS), 0, stream, p);
         else hipLaunchKernelGGL((box_cast_reduce_kernel<1, 0>), grid, dim3(BOX_THREADS), 0, stream, p);
-        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        return launch_status(__func__);
     }
     return SBP_ERR_UNSUPPORTED;
 }

@@ -1074,7 +1074,7 @@ int32_t launch_split(const GemmPlan& plan, int max_m, int max_n, hipStream_t st)
     else if (plan.b_kc) kern = gemm_split_kernel<false, true, F32_B>;
     else kern = gemm_split_kernel<false, false, F32_B>;
     hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, tile_order_for(tn));
-    return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    return launch_status(__func__);
 }
 
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
@@ -1092,14 +1092,14 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
         if (grid > nblk) grid = (int)nblk;
         hipLaunchKernelGGL((gemm_mfma_persist_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 100, EPI, OutT>), dim3((uint32_t)grid),
                            dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
-        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        return launch_status(__func__);
     }
     void (*kern)(GemmPlan, int, int, int);
     if constexpr (ODD >= 100) kern = nullptr;
     else if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
     else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
     hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn));
-    return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    return launch_status(__func__);
 }
 
 template <int BM, int BN, int WM, int WN, int ODD, int EPI, typename OutT>
@@ -1191,7 +1191,7 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         if (plan.out_dtype != SBP_F32 || plan.epilogue != SBP_EPI_NONE) return SBP_ERR_DTYPE;
         if (plan.f32_operand == 2) launch_generic_epi<true, false, float>(plan, grid, stream);
         else launch_generic_epi<false, true, float>(plan, grid, stream);
-        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        return launch_status(__func__);
     }
     const bool fast = mfma_ok(plan);
     if (variant == 1 || !fast) {
@@ -1205,7 +1205,7 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
             if (plan.out_dtype != SBP_F32) return SBP_ERR_DTYPE;
             launch_generic_epi<false, false, float>(plan, grid, stream);
         }
-        return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+        return launch_status(__func__);
     }
     bool k128 = true;   // every local reduction a whole number of four-stage rounds
     for (int g = 0; g < plan.groups; ++g)

@@ -55,6 +55,43 @@ void spans_of(const sbp_tensor_t* t, sbp_t s, int32_t k, std::vector<Span>& v) {
 bool overlap(const Span& a, const Span& b) { return a.lo < b.hi && b.lo < a.hi; }
 
 // outputs must be pairwise disjoint and disjoint from every input
+// Two-dimensional signatures (Sec. 3.3): s[0] places the tensor on the k0 groups, s[1] each group's
+// tensor on its k1 devices; device (a, b) is shard a * k1 + b.
+Local local_of2(int64_t rows, int64_t cols, const sbp_t* s, int32_t k0, int32_t k1, int32_t a, int32_t b) {
+    const Local n = local_of(rows, cols, s[0], k0, a);
+    return local_of(n.rows, n.cols, s[1], k1, b);
+}
+int32_t check_grid(int32_t k0, int32_t k1) {
+    if (k0 < 1 || k1 < 1 || (int64_t)k0 * k1 > SBP_MAX_K) return SBP_ERR_K;
+    return SBP_OK;
+}
+int32_t check_tensor2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t k1) {
+    if (!t || !t->shard || !s) return SBP_ERR_NULL;
+    if (t->rows < 0 || t->cols < 0) return SBP_ERR_SHAPE;
+    if (t->dtype != SBP_F32 && t->dtype != SBP_BF16) return SBP_ERR_DTYPE;
+    if (t->trans != 0) return SBP_ERR_UNSUPPORTED;
+    if (!is_sbp(s[0]) || !is_sbp(s[1])) return SBP_ERR_AXIS;
+    for (int32_t a = 0; a < k0; ++a)
+        for (int32_t b = 0; b < k1; ++b) {
+            const Local l = local_of2(t->rows, t->cols, s, k0, k1, a, b);
+            if (l.rows * l.cols == 0) continue;
+            void* p = t->shard[a * k1 + b];
+            if (!p) return SBP_ERR_NULL;
+            if (reinterpret_cast<uintptr_t>(p) & 15u) return SBP_ERR_ALIGN;
+        }
+    return SBP_OK;
+}
+void spans_of2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t k1, std::vector<Span>& v) {
+    for (int32_t a = 0; a < k0; ++a)
+        for (int32_t b = 0; b < k1; ++b) {
+            const Local l = local_of2(t->rows, t->cols, s, k0, k1, a, b);
+            const uintptr_t bytes = (uintptr_t)(l.rows * l.cols) * elem_bytes(t->dtype);
+            if (bytes == 0) continue;
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(t->shard[a * k1 + b]);
+            v.push_back({lo, lo + bytes});
+        }
+}
+
 int32_t check_alias(const std::vector<Span>& outs, const std::vector<Span>& ins) {
     for (size_t a = 0; a < outs.size(); ++a) {
         for (size_t b = a + 1; b < outs.size(); ++b)
@@ -193,8 +230,9 @@ int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t
     return sbp_matmul_ex(x, sx, w, sw, y, sy, k, stream, SBP_EPI_NONE);
 }
 
-int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
-                   void* stream) {
+// launch = false: every check, nothing enqueued (the 2-D entry validates all its 1-D parts first)
+static int32_t boxing_impl(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
+                           void* stream, bool launch) {
     if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
     if (!in || !out) return SBP_ERR_NULL;
     int32_t st;
@@ -222,7 +260,12 @@ int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, 
         plan.src[i] = in->shard[i];
         plan.dst[i] = out->shard[i];
     }
-    return launch_boxing(plan, static_cast<hipStream_t>(stream));
+    return launch ? launch_boxing(plan, static_cast<hipStream_t>(stream)) : SBP_OK;
+}
+
+int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
+                   void* stream) {
+    return boxing_impl(in, s_in, out, s_out, k, stream, true);
 }
 
 int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
@@ -257,6 +300,141 @@ int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* 
         plan.dst[i] = out->shard[i];
     }
     return launch_boxing_cast(plan, static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_infer_matmul_2d(const sbp_t* sx, const sbp_t* sw, sbp_t* sy) {
+    if (!sx || !sw || !sy) return SBP_ERR_NULL;
+    sbp_t y[2];
+    for (int d = 0; d < 2; ++d) {
+        const int32_t st = sbp_infer_matmul(sx[d], sw[d], &y[d]);
+        if (st != SBP_OK) return st;
+    }
+    sy[0] = y[0];
+    sy[1] = y[1];
+    return SBP_OK;
+}
+
+int32_t sbp_local_shape_2d(int64_t rows, int64_t cols, const sbp_t* s, int32_t k0, int32_t k1, int32_t a, int32_t b,
+                           int64_t* lr, int64_t* lc) {
+    if (!s || !lr || !lc) return SBP_ERR_NULL;
+    int32_t st;
+    if ((st = check_grid(k0, k1)) != SBP_OK) return st;
+    if (a < 0 || a >= k0 || b < 0 || b >= k1) return SBP_ERR_K;
+    if (rows < 0 || cols < 0) return SBP_ERR_SHAPE;
+    if (!is_sbp(s[0]) || !is_sbp(s[1])) return SBP_ERR_AXIS;
+    const Local l = local_of2(rows, cols, s, k0, k1, a, b);
+    *lr = l.rows;
+    *lc = l.cols;
+    return SBP_OK;
+}
+
+int32_t sbp_matmul_2d(const sbp_tensor_t* x, const sbp_t* sx, const sbp_tensor_t* w, const sbp_t* sw,
+                      const sbp_tensor_t* y, const sbp_t* sy_in, int32_t k0, int32_t k1, void* stream) {
+    int32_t st;
+    if ((st = check_grid(k0, k1)) != SBP_OK) return st;
+    if (!x || !w || !y || !sx || !sw) return SBP_ERR_NULL;
+    sbp_t sy[2];
+    if ((st = sbp_infer_matmul_2d(sx, sw, sy)) != SBP_OK) return st;
+    if (sy_in)
+        for (int d = 0; d < 2; ++d) {
+            if (sy_in[d] == SBP_AUTO) continue;
+            if (!is_sbp(sy_in[d])) return SBP_ERR_AXIS;
+            if (sy_in[d] != sy[d]) return SBP_ERR_SIGNATURE;
+        }
+    if ((st = check_tensor2(x, sx, k0, k1)) != SBP_OK) return st;
+    if ((st = check_tensor2(w, sw, k0, k1)) != SBP_OK) return st;
+    if ((st = check_tensor2(y, sy, k0, k1)) != SBP_OK) return st;
+    if (x->cols != w->rows || y->rows != x->rows || y->cols != w->cols) return SBP_ERR_SHAPE;
+    const bool px = is_partial(sx[0]) || is_partial(sx[1]), pw = is_partial(sw[0]) || is_partial(sw[1]);
+    const bool py = is_partial(sy[0]) || is_partial(sy[1]);
+    int32_t f32_operand = 0;
+    if (px && x->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    if (pw && w->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    if (x->dtype != w->dtype) {
+        if (px && x->dtype == SBP_F32) f32_operand = 1;
+        else if (pw && w->dtype == SBP_F32) f32_operand = 2;
+        else return SBP_ERR_DTYPE;
+    }
+    if (y->dtype != ((py || f32_operand) ? SBP_F32 : x->dtype)) return SBP_ERR_DTYPE;
+    if (x->rows > INT32_MAX || x->cols > INT32_MAX || w->cols > INT32_MAX) return SBP_ERR_UNSUPPORTED;
+
+    std::vector<Span> ins, outs;
+    spans_of2(x, sx, k0, k1, ins);
+    spans_of2(w, sw, k0, k1, ins);
+    spans_of2(y, sy, k0, k1, outs);
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    GemmPlan plan{};
+    plan.groups = k0 * k1;
+    plan.in_dtype = f32_operand ? SBP_BF16 : x->dtype;
+    plan.f32_operand = f32_operand;
+    plan.out_dtype = y->dtype;
+    plan.a_kc = 1;
+    plan.b_kc = 0;
+    plan.epilogue = SBP_EPI_NONE;
+    for (int32_t a = 0; a < k0; ++a)
+        for (int32_t b = 0; b < k1; ++b) {
+            const Local lx = local_of2(x->rows, x->cols, sx, k0, k1, a, b);
+            const Local lw = local_of2(w->rows, w->cols, sw, k0, k1, a, b);
+            const Local ly = local_of2(y->rows, y->cols, sy, k0, k1, a, b);
+            if (lx.cols != lw.rows || ly.rows != lx.rows || ly.cols != lw.cols) return SBP_ERR_SHAPE;
+            GemmShard& g = plan.s[a * k1 + b];
+            g.a = x->shard[a * k1 + b];
+            g.b = w->shard[a * k1 + b];
+            g.c = y->shard[a * k1 + b];
+            g.m = (int32_t)lx.rows;
+            g.n = (int32_t)lw.cols;
+            g.kk = (int32_t)lx.cols;
+            g.lda = (int32_t)lx.cols;
+            g.ldb = (int32_t)lw.cols;
+            g.ldc = (int32_t)ly.cols;
+        }
+    return launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_boxing_2d(const sbp_tensor_t* in, const sbp_t* s_in, const sbp_tensor_t* out, const sbp_t* s_out,
+                      int32_t k0, int32_t k1, void* stream) {
+    int32_t st;
+    if ((st = check_grid(k0, k1)) != SBP_OK) return st;
+    if (!in || !out || !s_in || !s_out) return SBP_ERR_NULL;
+    if ((st = check_tensor2(in, s_in, k0, k1)) != SBP_OK) return st;
+    if ((st = check_tensor2(out, s_out, k0, k1)) != SBP_OK) return st;
+    if (in->rows != out->rows || in->cols != out->cols) return SBP_ERR_SHAPE;
+    if (in->dtype != out->dtype) return SBP_ERR_DTYPE;
+    const bool inner = s_in[0] == s_out[0];
+    if (!inner && s_in[1] != s_out[1]) return SBP_ERR_UNSUPPORTED;   // one position at a time
+    const sbp_t keep = inner ? s_in[0] : s_in[1];
+    if (is_partial(keep) && in->dtype != SBP_F32) return SBP_ERR_DTYPE;
+    // outer conversion with an inner split: the devices of inner index b hold slice b of the tensor
+    // only if the conversion does not touch the axis the inner position splits
+    if (!inner && (keep == SBP_S(0) || keep == SBP_S(1)) && (s_in[0] == keep || s_out[0] == keep)) return SBP_ERR_UNSUPPORTED;
+
+    std::vector<Span> ins, outs;
+    spans_of2(in, s_in, k0, k1, ins);
+    spans_of2(out, s_out, k0, k1, outs);
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    const int32_t parts = inner ? k0 : k1, kk = inner ? k1 : k0;
+    std::vector<void*> pin((size_t)parts * kk), pout((size_t)parts * kk);
+    std::vector<sbp_tensor_t> tin(parts), tout(parts);
+    for (int32_t g = 0; g < parts; ++g) {
+        for (int32_t i = 0; i < kk; ++i) {
+            const int32_t dev = inner ? g * k1 + i : i * k1 + g;
+            pin[(size_t)g * kk + i] = in->shard[dev];
+            pout[(size_t)g * kk + i] = out->shard[dev];
+        }
+        // the tensor this group of devices holds between them
+        const Local l = inner ? local_of(in->rows, in->cols, keep, k0, g) : local_of(in->rows, in->cols, keep, k1, g);
+        tin[g] = {&pin[(size_t)g * kk], l.rows, l.cols, in->dtype, 0};
+        tout[g] = {&pout[(size_t)g * kk], l.rows, l.cols, out->dtype, 0};
+    }
+    const sbp_t a = inner ? s_in[1] : s_in[0], b = inner ? s_out[1] : s_out[0];
+    for (int pass = 0; pass < 2; ++pass)   // validate every part, then launch every part
+        for (int32_t g = 0; g < parts; ++g) {
+            if (tin[g].rows * tin[g].cols == 0) continue;
+            if ((st = boxing_impl(&tin[g], a, &tout[g], b, kk, stream, pass == 1)) != SBP_OK) return st;
+        }
+    return SBP_OK;
 }
 
 static int32_t row_stat(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* gmax, const sbp_tensor_t* out,

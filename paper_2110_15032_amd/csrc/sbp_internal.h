@@ -18,6 +18,15 @@ __host__ __device__ inline int64_t split_len(int64_t n, int32_t k, int32_t i) {
     return n / k + (i < n % k ? 1 : 0);
 }
 
+// Status of the launch just made; a failure is reported on stderr with HIP's own text (it means a
+// launch configuration the device refused, never a data-dependent condition).
+inline int32_t launch_status(const char* where) {
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return SBP_OK;
+    fprintf(stderr, "libsbp_mi355x: kernel launch in %s failed: %s\n", where, hipGetErrorString(e));
+    return SBP_ERR_LAUNCH;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Boxing: every conversion is a set of rectangle tasks.  Task t reads a rows x cols rectangle
 // from n_src source shards (all at the same offset / leading dimension), combines them

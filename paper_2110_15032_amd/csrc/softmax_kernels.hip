@@ -100,7 +100,7 @@ int32_t launch_row_stat(const RowStatPlan& plan, bool sumexp, hipStream_t stream
         if (bf) hipLaunchKernelGGL((row_stat_kernel<false, true>), grid, block, 0, stream, plan);
         else hipLaunchKernelGGL((row_stat_kernel<false, false>), grid, block, 0, stream, plan);
     }
-    return hipGetLastError() == hipSuccess ? SBP_OK : SBP_ERR_LAUNCH;
+    return launch_status(__func__);
 }
 
 }  // namespace sbp

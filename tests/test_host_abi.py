@@ -145,6 +145,24 @@ def test_boxing_cast_validation_errors():
     assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.S(0), over, sbp.B, k, st) == -7          # output over the input
 
 
+def test_2d_validation_errors():
+    k0, k1 = 2, 2
+    S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
+    x, w, y = fake(4, 8, 8), fake(4, 8, 8, base=0x20000000), fake(4, 8, 8, base=0x30000000)
+    st = 0
+    assert status_of(sbp.sbp_matmul_2d, x, (S0, S1), w, (B_, S1), y, None, k0, k1, st) == -6        # inner pair not in Table 1
+    assert status_of(sbp.sbp_matmul_2d, x, (S0, B_), w, (B_, S1), y, (S0, B_), k0, k1, st) == -6    # deduced is (S0, S1)
+    assert status_of(sbp.sbp_matmul_2d, x, (S0, B_), w, (B_, S1), y, None, 9, 9, st) == -2          # 81 devices
+    assert status_of(sbp.sbp_matmul_2d, x, (S0, S1), w, (B_, S0), fake(4, 8, 8, sbp.BF16, base=0x30000000), None, k0, k1, st) == -4
+    assert status_of(sbp.sbp_matmul_2d, x, (S0, B_), w, (B_, S1), x, None, k0, k1, st) == -7        # y over x
+    assert status_of(sbp.sbp_boxing_2d, x, (S0, P), y, (B_, B_), k0, k1, st) == -9                  # both entries change
+    assert status_of(sbp.sbp_boxing_2d, x, (S0, S0), y, (B_, S0), k0, k1, st) == -9                 # along the inner split's axis
+    assert status_of(sbp.sbp_boxing_2d, fake(4, 8, 8, sbp.BF16), (S0, P), fake(4, 8, 8, sbp.BF16, base=0x30000000), (S0, B_), k0, k1, st) == -4
+    assert status_of(sbp.sbp_boxing_2d, x, (S0, B_), x, (S0, S1), k0, k1, st) == -7
+    assert sbp.sbp_infer_matmul_2d((S0, S1), (B_, S0)) == (S0, P)
+    assert sbp.sbp_local_shape_2d(10, 7, (S0, S0), 2, 2, 1, 1) == (2, 7)
+
+
 def test_row_stat_validation_errors():
     k = 4
     L = fake(k, 16, 64, sbp.BF16)
