@@ -387,3 +387,70 @@ def row_sumexp(L, m) -> np.ndarray:
     s = np.empty(L.shape[0], dtype=np.float64)
     _c().orc_row_sumexp(_ptr(L), _ptr(m), L.shape[0], L.shape[1], _ptr(s))
     return s
+
+
+# ----------------------------------------------------------------------------
+# Sec. 6.3.1 continued: sparse cross entropy on model-parallel (S(1)) logits.
+# The figure that details the operators is lost in the source text; what is
+# computed is the textbook definition, loss[r] = -log softmax(L[r, :])[y[r]],
+# and its gradient, decomposed over the column shards the way the softmax is:
+# every device works on the columns it holds, using the global max m and
+# the global denominator s obtained by boxing (parity unpinned by the paper).
+# ----------------------------------------------------------------------------
+def softmax_xent_loss(L, labels) -> np.ndarray:
+    """loss[r] = log(sum_c exp(L[r, c])) - L[r, y[r]]; a label outside [0, C) marks an ignored row (0)."""
+    L = _f64(L)
+    labels = np.asarray(labels, dtype=np.int64)
+    m = L.max(axis=1)
+    lse = m + np.log(np.exp(L - m[:, None]).sum(axis=1))
+    ok = (labels >= 0) & (labels < L.shape[1])
+    picked = L[np.arange(L.shape[0]), np.where(ok, labels, 0)]
+    return np.where(ok, lse - picked, 0.0)
+
+
+def softmax_xent_grad(L, labels, g) -> np.ndarray:
+    """d loss[r] / d L[r, c] * g[r] = (softmax(L[r, :])[c] - [c == y[r]]) * g[r]; ignored rows get 0."""
+    L, g = _f64(L), _f64(g)
+    labels = np.asarray(labels, dtype=np.int64)
+    m = L.max(axis=1)
+    e = np.exp(L - m[:, None])
+    p = e / e.sum(axis=1)[:, None]
+    ok = (labels >= 0) & (labels < L.shape[1])
+    p[np.arange(L.shape[0])[ok], labels[ok]] -= 1.0
+    return p * np.where(ok, g, 0.0)[:, None]
+
+
+def xent_loss_sbp(Ls: list[np.ndarray], labels, m, s) -> list[np.ndarray]:
+    """Model-parallel form: Ls are the S(1) shards of the logits, m and s the global row max and
+    denominator.  The device that holds column y[r] contributes log s[r] + m[r] - L[r, y[r]], every
+    other device 0: k partial vectors, P(sum)."""
+    labels = np.asarray(labels, dtype=np.int64)
+    m, s = _f64(m), _f64(s)
+    out, begin = [], 0
+    for Li in Ls:
+        Li = _f64(Li)
+        mine = (labels >= begin) & (labels < begin + Li.shape[1])
+        v = np.zeros(Li.shape[0], dtype=np.float64)
+        rows = np.arange(Li.shape[0])[mine]
+        v[rows] = np.log(s[rows]) + m[rows] - Li[rows, labels[rows] - begin]
+        out.append(v)
+        begin += Li.shape[1]
+    return out
+
+
+def xent_grad_sbp(Ls: list[np.ndarray], labels, m, s, g) -> list[np.ndarray]:
+    """Model-parallel gradient: elementwise on every S(1) shard, no communication."""
+    labels = np.asarray(labels, dtype=np.int64)
+    m, s, g = _f64(m), _f64(s), _f64(g)
+    total = sum(Li.shape[1] for Li in Ls)
+    ok = (labels >= 0) & (labels < total)
+    out, begin = [], 0
+    for Li in Ls:
+        Li = _f64(Li)
+        p = np.exp(Li - m[:, None]) / s[:, None]
+        mine = (labels >= begin) & (labels < begin + Li.shape[1])
+        rows = np.arange(Li.shape[0])[mine]
+        p[rows, labels[rows] - begin] -= 1.0
+        out.append(p * np.where(ok, g, 0.0)[:, None])
+        begin += Li.shape[1]
+    return out

@@ -402,3 +402,51 @@ def test_pins_catch_a_transposed_or_missplit_oracle(monkeypatch):
     sh = impl.scatter(T, S0, 3)
     ref = np.array_split(T, 3, axis=0)
     assert any(a.shape != b.shape for a, b in zip(sh, ref))
+
+
+# ------------------------------------------------------------ sparse cross entropy (Sec. 6.3.1)
+def test_softmax_xent_against_scipy_and_finite_differences():
+    from scipy.special import log_softmax, softmax
+    R, C = 9, 23
+    L = RNG.standard_normal((R, C)) * 3.0
+    y = RNG.integers(0, C, size=R)
+    y[2] = -1                                        # ignored row
+    g = RNG.standard_normal(R)
+    loss = orc.softmax_xent_loss(L, y)
+    ref = -log_softmax(L, axis=1)[np.arange(R), np.where(y >= 0, y, 0)]
+    ref[2] = 0.0
+    assert np.allclose(loss, ref, rtol=1e-13, atol=1e-13)
+    grad = orc.softmax_xent_grad(L, y, g)
+    onehot = np.zeros((R, C))
+    onehot[np.arange(R)[y >= 0], y[y >= 0]] = 1.0
+    gg = np.where(y >= 0, g, 0.0)
+    assert np.allclose(grad, (softmax(L, axis=1) - onehot) * gg[:, None], rtol=1e-12, atol=1e-14)
+    assert np.allclose(grad.sum(axis=1), 0.0, atol=1e-14)          # softmax sums to one
+    assert np.all(grad[2] == 0.0)
+    # central differences of sum_r g[r] loss[r]
+    eps = 1e-6
+    for r, c in [(0, int(y[0])), (1, 5), (4, 0), (8, C - 1)]:
+        Lp, Lm = L.copy(), L.copy()
+        Lp[r, c] += eps
+        Lm[r, c] -= eps
+        num = (np.dot(gg, orc.softmax_xent_loss(Lp, y)) - np.dot(gg, orc.softmax_xent_loss(Lm, y))) / (2 * eps)
+        assert abs(num - grad[r, c]) < 1e-8
+
+
+@pytest.mark.parametrize("k", [1, 3, 8])
+def test_model_parallel_xent_is_the_plain_one_for_every_shard_count(k):
+    R, C = 7, 41
+    L = RNG.standard_normal((R, C)) * 2.0
+    y = RNG.integers(0, C, size=R)
+    y[5] = C + 3                                     # ignored row
+    g = RNG.standard_normal(R)
+    Ls = orc.scatter(L, S1, k)
+    m = orc.assemble([orc.row_max(s)[:, None] if s.shape[1] else np.full((R, 1), -np.inf) for s in Ls], P_MAX)[:, 0]
+    s = orc.assemble([orc.row_sumexp(x, m)[:, None] if x.shape[1] else np.zeros((R, 1)) for x in Ls], P_SUM)[:, 0]
+    parts = orc.xent_loss_sbp(Ls, y, m, s)
+    assert len(parts) == k
+    assert np.allclose(orc.assemble([p[:, None] for p in parts], P_SUM)[:, 0], orc.softmax_xent_loss(L, y), atol=1e-12)
+    # exactly one device contributes per (non-ignored) row
+    assert np.array_equal(sum((p != 0).astype(int) for p in parts), (np.arange(R) != 5).astype(int))
+    grads = orc.xent_grad_sbp(Ls, y, m, s, g)
+    assert np.allclose(orc.assemble(grads, S1), orc.softmax_xent_grad(L, y, g), atol=1e-13)
