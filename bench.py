@@ -303,7 +303,8 @@ def bench_dp_grad(args, cfg, sbp, wl, torch, np):
 
 
 def bench_classifier(args, cfg, sbp, wl, torch, np):
-    """logits = F W on 8 class shards (bf16), local row max -> P(max) -> B, local sum of exp -> P(sum) -> B."""
+    """logits = F W on 8 class shards (bf16), local row max -> P(max) -> B, local sum of exp -> P(sum) -> B,
+    then the sparse cross entropy: loss partials -> P(sum) -> B and the gradient of the logits (S(1))."""
     k = cfg["k"]
     R, Dm = cfg["F"]["shape"]
     C = cfg["W"]["shape"][1]
@@ -326,14 +327,22 @@ def bench_classifier(args, cfg, sbp, wl, torch, np):
     vec = lambda: arena([(R, 1)] * k, torch.float32)      # noqa: E731
     Ft, Wt = sbp.SbpTensor(f_sh, R, Dm, sbp.BF16), sbp.SbpTensor(w_sh, Dm, C, sbp.BF16)
     L = sbp.SbpTensor(l_sh, R, C, sbp.BF16)
-    MP, MB, SP, SB = (sbp.SbpTensor(vec(), R, 1, sbp.F32) for _ in range(4))
+    MP, MB, SP, SB, LP, LB, GR = (sbp.SbpTensor(vec(), R, 1, sbp.F32) for _ in range(7))
+    for t in GR.keep:
+        t.fill_(1.0 / R)
+    labels = torch.from_numpy((wl.uniform(seed, 7, (R, 1), 0.0, float(C)).astype(np.int64) % C).astype(np.int32)).cuda()
+    Y = sbp.SbpTensor([labels] * k, R, 1, sbp.I32)
+    DL = sbp.SbpTensor(arena([(R, Ci)] * k, torch.int16), R, C, sbp.BF16)
 
     def stages_of(s):
         return [lambda st: sbp.sbp_matmul(Ft, sbp.B, Wt, sbp.S(1), L, sbp.S(1), k, st),
                 lambda st: sbp.sbp_row_max(L, sbp.S(1), MP, k, st),
                 lambda st: sbp.sbp_boxing(MP, sbp.P_MAX, MB, sbp.B, k, st),
                 lambda st: sbp.sbp_row_sumexp(L, sbp.S(1), MB, SP, k, st),
-                lambda st: sbp.sbp_boxing(SP, sbp.P_SUM, SB, sbp.B, k, st)]
+                lambda st: sbp.sbp_boxing(SP, sbp.P_SUM, SB, sbp.B, k, st),
+                lambda st: sbp.sbp_xent_loss(L, sbp.S(1), Y, MB, SB, LP, k, st),
+                lambda st: sbp.sbp_boxing(LP, sbp.P_SUM, LB, sbp.B, k, st),
+                lambda st: sbp.sbp_xent_grad(L, sbp.S(1), Y, MB, SB, GR, DL, k, st)]
 
     ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
     flops = 2.0 * R * Dm * C
@@ -345,11 +354,14 @@ def bench_classifier(args, cfg, sbp, wl, torch, np):
                "row_max_ms": round(ms[1], 4), "row_max_gbps": round(lbytes / ms[1] / 1e6, 1),
                "boxing_pmax_us": round(ms[2] * 1e3, 1),
                "row_sumexp_ms": round(ms[3], 4), "row_sumexp_gbps": round(lbytes / ms[3] / 1e6, 1),
-               "boxing_psum_us": round(ms[4] * 1e3, 1)}
+               "boxing_psum_us": round(ms[4] * 1e3, 1),
+               "xent_loss_us": round(ms[5] * 1e3, 1), "boxing_loss_us": round(ms[6] * 1e3, 1),
+               "xent_grad_ms": round(ms[7], 4), "xent_grad_gbps": round(2 * lbytes / ms[7] / 1e6, 1),
+               "mean_loss": float(LB.keep[0].mean())}
     roof = {"bound": "mfma", "kernel": "sbp_matmul (B,S1)->S1 bf16 logits", "achieved": round(tf, 2),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
     return result_line(args, "model-parallel classifier head, k=8: F[1024,512] B x W[512,1000000] S(1) -> bf16 logits S(1); "
-                             "row max P(max)->B; sum exp(L - max) P(sum)->B",
+                             "row max P(max)->B; sum exp(L - max) P(sum)->B; sparse cross entropy loss P(sum)->B and gradient S(1)",
                        k, flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
 
 

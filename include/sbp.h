@@ -51,7 +51,7 @@ typedef int32_t sbp_t;
 #define SBP_AUTO    ((sbp_t)-100)   /* sbp_matmul only: "whatever Table 1 says" */
 
 /* ---- element types --------------------------------------------------------*/
-enum { SBP_F32 = 0, SBP_BF16 = 1 };
+enum { SBP_F32 = 0, SBP_BF16 = 1, SBP_I32 = 2 /* class labels of sbp_xent_* only */ };
 
 /* ---- status codes ---------------------------------------------------------*/
 enum {
@@ -73,7 +73,7 @@ enum {
 typedef struct sbp_tensor {
     void* const* shard; /* host array [k] of device pointers                          */
     int64_t rows, cols; /* GLOBAL shape; vectors are [n, 1]                           */
-    int32_t dtype;      /* SBP_F32 | SBP_BF16                                         */
+    int32_t dtype;      /* SBP_F32 | SBP_BF16 (SBP_I32 for label vectors)             */
     int32_t trans;      /* 0: shards hold the local tensor; 1: its transpose          */
 } sbp_tensor_t;
 
@@ -185,6 +185,25 @@ int32_t sbp_row_max(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_t*
                     int32_t k, void* stream);
 int32_t sbp_row_sumexp(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_t* gmax,
                        const sbp_tensor_t* out, int32_t k, void* stream);
+
+/* Sparse cross entropy on the same model-parallel logits (Sec. 6.3.1: MatMul, softmax and sparse
+ * cross entropy with the weight S(1)).  logits [R,C] S(1), bf16 or f32.  labels [R,1] SBP_I32, B:
+ * the class of every row; a value outside [0, C) marks a row that is ignored.  gmax, denom [R,1]
+ * f32, B: the global row max and softmax denominator (sbp_row_max / sbp_row_sumexp, each boxed to
+ * B).  Vectors are passed as k device pointers like every B tensor (copies may share one buffer).
+ *   sbp_xent_loss: loss [R,1] f32 P(sum).  The device that holds column y[r] writes
+ *                  log denom[r] + gmax[r] - L[r, y[r]], every other device (and every ignored
+ *                  row) 0; boxing P(sum) -> B gives -log softmax(L[r,:])[y[r]].
+ *   sbp_xent_grad: dlogits [R,C] S(1), dtype of logits:
+ *                  (exp(L[r,c] - gmax[r]) / denom[r] - [c == y[r]]) * grad[r], grad [R,1] f32 B the
+ *                  upstream gradient of every row's loss; ignored rows get 0.  Elementwise, no
+ *                  communication.  One rounding to nearest even for bf16.
+ * At most 32 devices (SBP_ERR_UNSUPPORTED beyond); sbp_l other than S(1) as for sbp_row_max. */
+int32_t sbp_xent_loss(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_t* labels, const sbp_tensor_t* gmax,
+                      const sbp_tensor_t* denom, const sbp_tensor_t* loss, int32_t k, void* stream);
+int32_t sbp_xent_grad(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_t* labels, const sbp_tensor_t* gmax,
+                      const sbp_tensor_t* denom, const sbp_tensor_t* grad, const sbp_tensor_t* dlogits, int32_t k,
+                      void* stream);
 
 /* Tuning knobs; they never change what is computed beyond fp32 summation order
  * inside a GEMM tile.  Unknown knob or value: SBP_ERR_UNSUPPORTED. */

@@ -19,6 +19,7 @@ AUTO = -100
 # dtypes
 F32 = 0
 BF16 = 1
+I32 = 2
 # epilogues
 EPI_NONE = 0
 EPI_GELU = 1
@@ -29,7 +30,7 @@ KNOB_TILE_ORDER = 1
 #: every symbol include/sbp.h declares
 EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing", "sbp_boxing_cast",
            "sbp_infer_matmul_2d", "sbp_local_shape_2d", "sbp_matmul_2d", "sbp_boxing_2d",
-           "sbp_row_max", "sbp_row_sumexp", "sbp_set_knob", "sbp_strerror")
+           "sbp_row_max", "sbp_row_sumexp", "sbp_xent_loss", "sbp_xent_grad", "sbp_set_knob", "sbp_strerror")
 
 
 class _CTensor(ctypes.Structure):
@@ -81,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.sbp_boxing_2d.argtypes = [T, P2, T, P2, i32, i32, vp]
         L.sbp_row_max.argtypes = [T, i32, T, i32, vp]
         L.sbp_row_sumexp.argtypes = [T, i32, T, T, i32, vp]
+        L.sbp_xent_loss.argtypes = [T, i32, T, T, T, T, i32, vp]
+        L.sbp_xent_grad.argtypes = [T, i32, T, T, T, T, T, i32, vp]
         L.sbp_set_knob.argtypes = [i32, i32]
         L.sbp_strerror.argtypes = [i32]
         L.sbp_strerror.restype = ctypes.c_char_p
@@ -190,6 +193,18 @@ def sbp_row_max(logits: SbpTensor, sbp_l: int, out: SbpTensor, k: int, stream=No
 
 def sbp_row_sumexp(logits: SbpTensor, sbp_l: int, gmax: SbpTensor, out: SbpTensor, k: int, stream=None) -> None:
     _check(lib().sbp_row_sumexp(logits.ref(), sbp_l, gmax.ref(), out.ref(), k, _stream_ptr(stream)), "sbp_row_sumexp")
+
+
+def sbp_xent_loss(logits: SbpTensor, sbp_l: int, labels: SbpTensor, gmax: SbpTensor, denom: SbpTensor, loss: SbpTensor,
+                  k: int, stream=None) -> None:
+    _check(lib().sbp_xent_loss(logits.ref(), sbp_l, labels.ref(), gmax.ref(), denom.ref(), loss.ref(), k,
+                               _stream_ptr(stream)), "sbp_xent_loss")
+
+
+def sbp_xent_grad(logits: SbpTensor, sbp_l: int, labels: SbpTensor, gmax: SbpTensor, denom: SbpTensor, grad: SbpTensor,
+                  dlogits: SbpTensor, k: int, stream=None) -> None:
+    _check(lib().sbp_xent_grad(logits.ref(), sbp_l, labels.ref(), gmax.ref(), denom.ref(), grad.ref(), dlogits.ref(), k,
+                               _stream_ptr(stream)), "sbp_xent_grad")
 
 
 def sbp_set_knob(knob: int, value: int) -> None:

@@ -472,6 +472,86 @@ static int32_t row_stat(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t
     return launch_row_stat(plan, sumexp, static_cast<hipStream_t>(stream));
 }
 
+// labels: [R,1] SBP_I32, B (one device pointer per logical device; copies may share a buffer)
+static int32_t check_vector(const sbp_tensor_t* t, int64_t rows, int32_t dtype, int32_t k) {
+    if (!t || !t->shard) return SBP_ERR_NULL;
+    if (t->rows != rows || t->cols != 1) return SBP_ERR_SHAPE;
+    if (t->dtype != dtype) return SBP_ERR_DTYPE;
+    if (t->trans) return SBP_ERR_UNSUPPORTED;
+    for (int32_t i = 0; i < k && rows > 0; ++i) {
+        if (!t->shard[i]) return SBP_ERR_NULL;
+        if (reinterpret_cast<uintptr_t>(t->shard[i]) & 15u) return SBP_ERR_ALIGN;
+    }
+    return SBP_OK;
+}
+static void spans_of_vector(const sbp_tensor_t* t, int32_t k, std::vector<Span>& v) {
+    for (int32_t i = 0; i < k; ++i) {
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(t->shard[i]);
+        if (t->rows) v.push_back({lo, lo + (uintptr_t)t->rows * 4});
+    }
+}
+
+static int32_t xent(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* labels, const sbp_tensor_t* gmax,
+                    const sbp_tensor_t* denom, const sbp_tensor_t* grad, const sbp_tensor_t* out, int32_t k, void* stream) {
+    if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
+    if (!logits || !labels || !gmax || !denom || !out) return SBP_ERR_NULL;
+    int32_t st;
+    if ((st = check_tensor(logits, sl, k)) != SBP_OK) return st;
+    if (sl != SBP_S(1)) return is_partial(sl) ? SBP_ERR_SIGNATURE : SBP_ERR_UNSUPPORTED;
+    if (k > XENT_MAX_K) return SBP_ERR_UNSUPPORTED;
+    if (logits->trans) return SBP_ERR_UNSUPPORTED;
+    if (logits->cols > INT32_MAX || logits->rows > INT32_MAX) return SBP_ERR_UNSUPPORTED;
+    const int64_t R = logits->rows;
+    if ((st = check_vector(labels, R, SBP_I32, k)) != SBP_OK) return st;
+    if ((st = check_vector(gmax, R, SBP_F32, k)) != SBP_OK) return st;
+    if ((st = check_vector(denom, R, SBP_F32, k)) != SBP_OK) return st;
+    if (grad && (st = check_vector(grad, R, SBP_F32, k)) != SBP_OK) return st;
+    std::vector<Span> ins, outs;
+    spans_of(logits, sl, k, ins);
+    spans_of_vector(labels, k, ins);
+    spans_of_vector(gmax, k, ins);
+    spans_of_vector(denom, k, ins);
+    if (grad) {
+        spans_of_vector(grad, k, ins);
+        if ((st = check_tensor(out, SBP_S(1), k)) != SBP_OK) return st;
+        if (out->rows != R || out->cols != logits->cols || out->dtype != logits->dtype || out->trans) return SBP_ERR_SHAPE;
+        spans_of(out, SBP_S(1), k, outs);
+    } else {
+        if ((st = check_vector(out, R, SBP_F32, k)) != SBP_OK) return st;
+        spans_of_vector(out, k, outs);
+    }
+    if ((st = check_alias(outs, ins)) != SBP_OK) return st;
+
+    XentPlan plan{};
+    plan.rows = R;
+    plan.total_cols = (int32_t)logits->cols;
+    plan.k = k;
+    plan.dtype = logits->dtype;
+    for (int32_t i = 0; i < k; ++i) {
+        plan.logits[i] = logits->shard[i];
+        plan.labels[i] = static_cast<const int32_t*>(labels->shard[i]);
+        plan.gmax[i] = static_cast<const float*>(gmax->shard[i]);
+        plan.denom[i] = static_cast<const float*>(denom->shard[i]);
+        plan.grad[i] = grad ? static_cast<const float*>(grad->shard[i]) : nullptr;
+        plan.out[i] = out->shard[i];
+        plan.cols[i] = (int32_t)split_len(logits->cols, k, i);
+        plan.begin[i] = (int32_t)split_begin(logits->cols, k, i);
+    }
+    return grad ? launch_xent_grad(plan, static_cast<hipStream_t>(stream)) : launch_xent_loss(plan, static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_xent_loss(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* labels, const sbp_tensor_t* gmax,
+                      const sbp_tensor_t* denom, const sbp_tensor_t* loss, int32_t k, void* stream) {
+    return xent(logits, sl, labels, gmax, denom, nullptr, loss, k, stream);
+}
+
+int32_t sbp_xent_grad(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* labels, const sbp_tensor_t* gmax,
+                      const sbp_tensor_t* denom, const sbp_tensor_t* grad, const sbp_tensor_t* dlogits, int32_t k,
+                      void* stream) {
+    if (!grad) return SBP_ERR_NULL;
+    return xent(logits, sl, labels, gmax, denom, grad, dlogits, k, stream);
+}
+
 int32_t sbp_row_max(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* out, int32_t k, void* stream) {
     return row_stat(logits, sl, nullptr, out, k, stream, false);
 }

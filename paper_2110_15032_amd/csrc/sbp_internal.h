@@ -85,6 +85,25 @@ struct RowStatPlan {
     int32_t k;
     int32_t dtype;
 };
+// Sparse cross entropy on S(1) logits.  Arrays sized for 32 shards keep the argument block small.
+constexpr int XENT_MAX_K = 32;
+struct XentPlan {
+    const void* logits[XENT_MAX_K];
+    const int32_t* labels[XENT_MAX_K];
+    const float* gmax[XENT_MAX_K];
+    const float* denom[XENT_MAX_K];
+    const float* grad[XENT_MAX_K];   // backward only
+    void* out[XENT_MAX_K];           // loss partials (f32) or dlogits (dtype)
+    int32_t cols[XENT_MAX_K];        // local column count (= row pitch)
+    int32_t begin[XENT_MAX_K];       // first global column of the shard
+    int64_t rows;
+    int32_t total_cols;
+    int32_t k;
+    int32_t dtype;
+};
+int32_t launch_xent_loss(const XentPlan& plan, hipStream_t stream);
+int32_t launch_xent_grad(const XentPlan& plan, hipStream_t stream);
+
 int32_t launch_row_stat(const RowStatPlan& plan, bool sumexp, hipStream_t stream);
 
 }  // namespace sbp

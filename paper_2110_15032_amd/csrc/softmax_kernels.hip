@@ -85,7 +85,116 @@ __global__ __launch_bounds__(RS_THREADS) void row_stat_kernel(RowStatPlan p) {
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Sparse cross entropy on the same S(1) logits (Sec. 6.3.1): with the global row max m and
+// denominator s in hand (B), the loss needs one logit per row, held by exactly one device, so every
+// device writes a partial vector (P(sum)); the gradient is elementwise on every shard.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(RS_THREADS) void xent_loss_kernel(XentPlan p) {
+    const int i = blockIdx.y;
+    const int64_t r = (int64_t)blockIdx.x * RS_THREADS + threadIdx.x;
+    if (r >= p.rows) return;
+    const int32_t c = p.labels[i][r] - p.begin[i];
+    float out = 0.0f;
+    if (c >= 0 && c < p.cols[i]) {
+        const int64_t pos = r * p.cols[i] + c;
+        float l;
+        if constexpr (BF16) l = __uint_as_float((uint32_t) static_cast<const uint16_t*>(p.logits[i])[pos] << 16);
+        else l = static_cast<const float*>(p.logits[i])[pos];
+        out = logf(p.denom[i][r]) + p.gmax[i][r] - l;
+    }
+    static_cast<float*>(p.out[i])[r] = out;
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// VE elements per lane: 8 bf16 / 4 fp32 (16 bytes) when the row pitch allows, else 1
+template <bool BF16, int VE>
+__global__ __launch_bounds__(RS_THREADS) void xent_grad_kernel(XentPlan p) {
+    const int i = blockIdx.y;
+    const uint32_t cols_v = (uint32_t)p.cols[i] / VE;
+    const uint64_t total = (uint64_t)p.rows * cols_v;
+    const uint64_t stride = (uint64_t)gridDim.x * RS_THREADS;
+    for (uint64_t idx = (uint64_t)blockIdx.x * RS_THREADS + threadIdx.x; idx < total; idx += stride) {
+        const uint32_t r = (uint32_t)(idx / cols_v);
+        const uint32_t c = (uint32_t)(idx - (uint64_t)r * cols_v) * VE;
+        const int32_t y = p.labels[i][r];
+        const bool live = y >= 0 && y < p.total_cols;
+        const float g = live ? p.grad[i][r] : 0.0f;
+        const float m = p.gmax[i][r], inv = 1.0f / p.denom[i][r];
+        const int32_t yc = y - p.begin[i] - (int32_t)c;   // position of the label inside this group, if any
+        const int64_t pos = (int64_t)r * p.cols[i] + c;
+        float v[VE];
+        if constexpr (BF16 && VE == 8) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.logits[i]) + pos);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                v[2 * d] = bf16_lo(w[d]);
+                v[2 * d + 1] = bf16_hi(w[d]);
+            }
+        } else if constexpr (!BF16 && VE == 4) {
+            const f32x4 w = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.logits[i]) + pos);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = w[e];
+        } else {
+            if constexpr (BF16) v[0] = __uint_as_float((uint32_t) static_cast<const uint16_t*>(p.logits[i])[pos] << 16);
+            else v[0] = static_cast<const float*>(p.logits[i])[pos];
+        }
+#pragma unroll
+        for (int e = 0; e < VE; ++e) v[e] = (__expf(v[e] - m) * inv - (e == yc ? 1.0f : 0.0f)) * g;
+        if constexpr (BF16 && VE == 8) {
+            const u32x4 o = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.out[i]) + pos));
+        } else if constexpr (!BF16 && VE == 4) {
+            const f32x4 o = {v[0], v[1], v[2], v[3]};
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(static_cast<float*>(p.out[i]) + pos));
+        } else {
+            if constexpr (BF16) static_cast<uint16_t*>(p.out[i])[pos] = (uint16_t)(pack_bf16(v[0], 0.0f) & 0xFFFFu);
+            else static_cast<float*>(p.out[i])[pos] = v[0];
+        }
+    }
+}
+
 }  // namespace
+
+int32_t launch_xent_loss(const XentPlan& plan, hipStream_t stream) {
+    if (plan.rows == 0) return SBP_OK;
+    const int64_t bx = (plan.rows + RS_THREADS - 1) / RS_THREADS;
+    if (bx > 0x7FFFFFFF) return SBP_ERR_UNSUPPORTED;
+    const dim3 grid((uint32_t)bx, (uint32_t)plan.k);
+    if (plan.dtype == SBP_BF16) hipLaunchKernelGGL(xent_loss_kernel<true>, grid, dim3(RS_THREADS), 0, stream, plan);
+    else hipLaunchKernelGGL(xent_loss_kernel<false>, grid, dim3(RS_THREADS), 0, stream, plan);
+    return launch_status(__func__);
+}
+
+int32_t launch_xent_grad(const XentPlan& plan, hipStream_t stream) {
+    if (plan.rows == 0 || plan.total_cols == 0) return SBP_OK;
+    const bool bf = plan.dtype == SBP_BF16;
+    const int epv = bf ? 8 : 4;
+    bool vec = true;
+    int64_t max_units = 0;
+    for (int i = 0; i < plan.k; ++i) {
+        if (plan.cols[i] % epv) vec = false;
+        max_units = plan.cols[i] > max_units ? plan.cols[i] : max_units;
+    }
+    max_units = max_units * plan.rows / (vec ? epv : 1);
+    int64_t bx = (max_units + RS_THREADS - 1) / RS_THREADS;
+    const int64_t cap = (1 << 20) / plan.k;      // one pass up to a million workgroups, grid-stride beyond
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    const dim3 grid((uint32_t)bx, (uint32_t)plan.k);
+    if (bf && vec) hipLaunchKernelGGL((xent_grad_kernel<true, 8>), grid, dim3(RS_THREADS), 0, stream, plan);
+    else if (bf) hipLaunchKernelGGL((xent_grad_kernel<true, 1>), grid, dim3(RS_THREADS), 0, stream, plan);
+    else if (vec) hipLaunchKernelGGL((xent_grad_kernel<false, 4>), grid, dim3(RS_THREADS), 0, stream, plan);
+    else hipLaunchKernelGGL((xent_grad_kernel<false, 1>), grid, dim3(RS_THREADS), 0, stream, plan);
+    return launch_status(__func__);
+}
 
 int32_t launch_row_stat(const RowStatPlan& plan, bool sumexp, hipStream_t stream) {
     if (plan.rows == 0) return SBP_OK;

@@ -497,3 +497,62 @@ def test_model_parallel_softmax_statistics(k, cols):
         assert np.allclose(g, s[0], rtol=1e-5, atol=0)
     for j in range(1, k):
         assert_bits_equal(s_b.host()[j], s_b.host()[0], "denominator copies")
+
+
+@pytest.mark.parametrize("k", [1, 4, 8])
+@pytest.mark.parametrize("cols,dtype", [(4 * 8 * 40, "bf16"), (1003, "bf16"), (8 * 4 * 30, "f32")])
+def test_model_parallel_sparse_cross_entropy(k, cols, dtype):
+    """Sec. 6.3.1 continued: softmax statistics (max -> B, sum exp -> B), then the loss partials
+    (P(sum) -> B) and the gradient (S(1), elementwise), against the oracle's model-parallel forms and
+    through them against the plain definitions."""
+    rows = 37
+    torch = __import__("torch")
+    if dtype == "bf16":
+        L = rnd_bf16(9, (rows, cols), 3.0)
+    else:
+        L = (rnd_f32(9, (rows, cols)) * 3.0).astype(np.float32)
+    np_dt = L.dtype
+    y = (wl.uniform(SEED, 11, (rows, 1), 0.0, float(cols)).astype(np.int64) % cols).astype(np.int32)
+    y[3, 0] = -1                    # two ignored rows
+    y[7, 0] = cols + 5
+    g = rnd_f32(12, (rows, 1))
+    Ls = orc.scatter(L, orc.S1, k)
+    d_l = DevTensor.from_host(Ls, rows, cols, orc.S1)
+    vec = lambda sig: DevTensor.empty(rows, 1, np.float32, sig, k)      # noqa: E731
+    m_p, m_b, s_p, s_b, l_p, l_b = vec(orc.P_MAX), vec(orc.B), vec(orc.P_SUM), vec(orc.B), vec(orc.P_SUM), vec(orc.B)
+    d_g = DevTensor.from_host([g] * k, rows, 1, orc.B)
+    y_dev = [torch.from_numpy(y.copy()).cuda() for _ in range(k)]
+    d_y = sbp.SbpTensor(y_dev, rows, 1, sbp.I32)
+    d_dl = DevTensor.empty(rows, cols, np_dt, orc.S1, k)
+    sbp.sbp_row_max(d_l.desc, sbp.S(1), m_p.desc, k)
+    sbp.sbp_boxing(m_p.desc, sbp.P_MAX, m_b.desc, sbp.B, k)
+    sbp.sbp_row_sumexp(d_l.desc, sbp.S(1), m_b.desc, s_p.desc, k)
+    sbp.sbp_boxing(s_p.desc, sbp.P_SUM, s_b.desc, sbp.B, k)
+    sbp.sbp_xent_loss(d_l.desc, sbp.S(1), d_y, m_b.desc, s_b.desc, l_p.desc, k)
+    sbp.sbp_boxing(l_p.desc, sbp.P_SUM, l_b.desc, sbp.B, k)
+    sbp.sbp_xent_grad(d_l.desc, sbp.S(1), d_y, m_b.desc, s_b.desc, d_g.desc, d_dl.desc, k)
+    sync()
+    Lv = [values(s) for s in Ls]
+    m = m_b.host()[0][:, 0].astype(np.float64)
+    s = s_b.host()[0][:, 0].astype(np.float64)
+    # loss partials against the oracle's, fed with the GPU's own m and s (both fp32 images)
+    ref_parts = orc.xent_loss_sbp(Lv, y[:, 0], m, s)
+    for i, got in enumerate(l_p.host()):
+        assert np.allclose(got[:, 0], ref_parts[i], rtol=2e-6, atol=2e-6), f"loss partial {i}"
+    loss = l_b.host()[0][:, 0]
+    plain = orc.softmax_xent_loss(values(L), y[:, 0])
+    assert np.allclose(loss, plain, rtol=1e-5, atol=1e-5), "loss against the plain definition"
+    assert loss[3] == 0.0 and loss[7] == 0.0
+    for j in range(1, k):
+        assert_bits_equal(l_b.host()[j], l_b.host()[0], "loss copies")
+    # gradient
+    ref_g = orc.xent_grad_sbp(Lv, y[:, 0], m, s, g[:, 0])
+    plain_g = orc.scatter(orc.softmax_xent_grad(values(L), y[:, 0], g[:, 0]), orc.S1, k)
+    for i, got in enumerate(d_dl.host()):
+        gv = values(got)
+        tol = 2.0 ** -7 if dtype == "bf16" else 2e-5       # one bf16 rounding step / fp32 exp
+        assert gv.shape == ref_g[i].shape
+        assert np.all(np.abs(gv - ref_g[i]) <= tol * np.abs(ref_g[i]) + 1e-12), f"gradient shard {i}"
+        assert np.all(np.abs(gv - plain_g[i]) <= 2 * tol * np.abs(plain_g[i]) + 1e-7), f"gradient shard {i} vs plain"
+        if gv.size:
+            assert np.all(gv[3] == 0.0) and np.all(gv[7] == 0.0)

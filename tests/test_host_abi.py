@@ -163,6 +163,26 @@ def test_2d_validation_errors():
     assert sbp.sbp_local_shape_2d(10, 7, (S0, S0), 2, 2, 1, 1) == (2, 7)
 
 
+def test_xent_validation_errors():
+    k = 4
+    L = fake(k, 16, 64, sbp.BF16)
+    vec = lambda base, dt=sbp.F32: fake(k, 16, 1, dt, base=base)      # noqa: E731
+    y, m, s, g, loss = vec(0x20000000, sbp.I32), vec(0x30000000), vec(0x40000000), vec(0x50000000), vec(0x60000000)
+    dl = fake(k, 16, 64, sbp.BF16, base=0x70000000)
+    st = 0
+    assert status_of(sbp.sbp_xent_loss, L, sbp.S(0), y, m, s, loss, k, st) == -9
+    assert status_of(sbp.sbp_xent_loss, L, sbp.S(1), vec(0x20000000), m, s, loss, k, st) == -4      # labels must be I32
+    assert status_of(sbp.sbp_xent_loss, L, sbp.S(1), y, fake(k, 15, 1, base=0x30000000), s, loss, k, st) == -3
+    assert status_of(sbp.sbp_xent_loss, L, sbp.S(1), y, m, s, m, k, st) == -7                       # loss over gmax
+    assert status_of(sbp.sbp_xent_grad, L, sbp.S(1), y, m, s, g, fake(k, 16, 64, base=0x70000000), k, st) == -3   # dtype of logits
+    assert status_of(sbp.sbp_xent_grad, L, sbp.S(1), y, m, s, g, L, k, st) == -7                    # in place
+    big = 40
+    assert status_of(sbp.sbp_xent_loss, fake(big, 16, 64, sbp.BF16, step=0x10000), sbp.S(1), fake(big, 16, 1, sbp.I32, base=0x20000000, step=0x1000),
+                     fake(big, 16, 1, base=0x30000000, step=0x1000), fake(big, 16, 1, base=0x40000000, step=0x1000),
+                     fake(big, 16, 1, base=0x60000000, step=0x1000), big, st) == -9                 # more than 32 devices
+    del dl
+
+
 def test_row_stat_validation_errors():
     k = 4
     L = fake(k, 16, 64, sbp.BF16)
