@@ -14,9 +14,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// SUMEXP: m is passed as -max * log2(e), so that exp(v - max) is one FMA and one hardware exp2
+// (relative error about |v - max| * 1e-7: the argument is at most 0 and a term below 2^-126 adds
+// nothing to a sum that contains exp(0) = 1 somewhere on the row's devices)
+constexpr float LOG2E = 1.4426950408889634f;
 template <bool SUMEXP>
 __device__ inline float fold(float acc, float v, float m) {
-    if constexpr (SUMEXP) return acc + expf(v - m);
+    if constexpr (SUMEXP) return acc + __builtin_amdgcn_exp2f(fmaf(v, LOG2E, m));
     else return fmaxf(acc, v);
 }
 
@@ -36,7 +40,7 @@ __global__ __launch_bounds__(RS_THREADS) void row_stat_kernel(RowStatPlan p) {
     const int64_t row = blockIdx.x;
     const int32_t cols = p.cols[shard];
     const float ident = SUMEXP ? 0.0f : -INFINITY;
-    const float m = SUMEXP ? p.gmax[shard][row] : 0.0f;
+    const float m = SUMEXP ? -p.gmax[shard][row] * LOG2E : 0.0f;
     float acc = ident;
     if (cols > 0) {
         constexpr int EPV = BF16 ? 8 : 4;  // elements per 16-byte vector
