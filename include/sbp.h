@@ -118,6 +118,15 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w,
                       const sbp_tensor_t* y, sbp_t sbp_y, int32_t k, void* stream,
                       int32_t epilogue);
 
+/* sbp_matmul for a column-split result (Table 1 row 2, sbp_y = S(1) or SBP_AUTO) that also
+ * delivers the first statistic of the model-parallel softmax (Sec. 6.3.1): rowmax [M,1] f32,
+ * P(max), rowmax_i[r] = max over the columns device i holds of y as stored (for bf16 results: of
+ * the rounded values), exactly what sbp_row_max(y) gives, without the second pass over y where
+ * the GEMM kernel can fold it into its stores.  rowmax shards must not overlap x, w or y. */
+int32_t sbp_matmul_rowmax(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t* w, sbp_t sbp_w,
+                          const sbp_tensor_t* y, sbp_t sbp_y, const sbp_tensor_t* rowmax, int32_t k,
+                          void* stream);
+
 /* Boxing (Sec. 3.2, Table 2, same device set): rewrite the k local tensors of one
  * global tensor from sbp_in to sbp_out; the global tensor is unchanged.
  *   P(sum)/P(max) -> B      all-reduce:      out_j = op_i in_i            for every j

@@ -28,7 +28,7 @@ KNOB_GEMM_VARIANT = 0
 KNOB_TILE_ORDER = 1
 
 #: every symbol include/sbp.h declares
-EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_boxing", "sbp_boxing_cast",
+EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_matmul_rowmax", "sbp_boxing", "sbp_boxing_cast",
            "sbp_infer_matmul_2d", "sbp_local_shape_2d", "sbp_matmul_2d", "sbp_boxing_2d",
            "sbp_row_max", "sbp_row_sumexp", "sbp_xent_loss", "sbp_xent_grad", "sbp_set_knob", "sbp_strerror")
 
@@ -73,6 +73,7 @@ def lib() -> ctypes.CDLL:
         L.sbp_local_shape.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.sbp_matmul.argtypes = [T, i32, T, i32, T, i32, i32, vp]
         L.sbp_matmul_ex.argtypes = [T, i32, T, i32, T, i32, i32, vp, i32]
+        L.sbp_matmul_rowmax.argtypes = [T, i32, T, i32, T, i32, T, i32, vp]
         L.sbp_boxing.argtypes = [T, i32, T, i32, i32, vp]
         L.sbp_boxing_cast.argtypes = [T, i32, T, i32, i32, vp]
         P2 = ctypes.POINTER(i32)
@@ -149,6 +150,12 @@ def sbp_matmul_ex(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTens
                   stream=None, epilogue: int = EPI_NONE) -> None:
     _check(lib().sbp_matmul_ex(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, k, _stream_ptr(stream), epilogue),
            "sbp_matmul_ex")
+
+
+def sbp_matmul_rowmax(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTensor, sbp_y: int, rowmax: SbpTensor,
+                      k: int, stream=None) -> None:
+    _check(lib().sbp_matmul_rowmax(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, rowmax.ref(), k, _stream_ptr(stream)),
+           "sbp_matmul_rowmax")
 
 
 def sbp_boxing(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:

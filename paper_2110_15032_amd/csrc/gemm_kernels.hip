@@ -314,6 +314,22 @@ __device__ inline float mfma_epilogue(float v) {
 constexpr int STAGE_BYTES = 4096;
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }   // s_waitcnt vmcnt(n), nothing else
 
+// Row maximum of stored results (model-parallel softmax, Sec. 6.3.1, fused into the logits GEMM):
+// max over fp32 bit patterns with one integer atomic, signed max for non-negative values and unsigned
+// min for negative ones (both orders agree with the float order on their half; -0 is folded to +0
+// first).  Issued as inline assembly like the other stores of the persistent kernel.  The target
+// starts at -inf (fill_rowmax_kernel).
+__device__ inline void atomic_max_f32_untracked(float* a, float v) {
+    v += 0.0f;
+    if (v >= 0.0f) asm volatile("global_atomic_smax %0, %1, off" : : "v"(a), "v"(v) : "memory");
+    else asm volatile("global_atomic_umin %0, %1, off" : : "v"(a), "v"(v) : "memory");
+}
+__global__ __launch_bounds__(256) void fill_rowmax_kernel(GemmPlan p) {
+    const GemmShard& s = p.s[blockIdx.y];
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r < s.m) s.rowmax[r] = -__builtin_inff();
+}
+
 // 16-byte streaming store the compiler does not track.  The two idle cycles cover the hardware's
 // rule that the data registers of a store wider than 8 bytes must not be rewritten right behind it
 // (the compiler inserts them for stores it knows; here it cannot).
@@ -379,6 +395,13 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
         } else {
             static_assert(FN % 2 == 0, "bf16 results are staged in strips of two 32-column blocks");
             const int odd = lane & 1;
+            [[maybe_unused]] float rm[FM][4];   // EPI_ROWMAX: maxima of rows 32 i + 8 q + lane / 8 over this wave's columns
+            if constexpr (EPI == EPI_ROWMAX) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) rm[i][q] = -__builtin_inff();
+            }
             int w0 = wave * STAGE_BYTES + (4 * h + odd) * 128 + h * 64 + (c >> 1) * 4;         // block j even
             int w1 = wave * STAGE_BYTES + (4 * h + odd) * 128 + (1 - h) * 64 + (c >> 1) * 4;   // block j odd
             asm volatile("" : "+v"(w0));
@@ -403,6 +426,17 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
                     constexpr int q = decltype(qidx)::value;
                     const u32x4 v = *reinterpret_cast<const u32x4*>(stage + (rd + q * 1024));
                     u32x4* dst = reinterpret_cast<u32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + jp * 64);
+                    if constexpr (EPI == EPI_ROWMAX) {
+                        // this lane's 8 stored values, then the 8 lanes that share the row (quads, then
+                        // the two quads of the group through the half-row mirror)
+                        float mx = fmaxf(__uint_as_float(v[0] << 16), __uint_as_float(v[0] & 0xFFFF0000u));
+#pragma unroll
+                        for (int d = 1; d < 4; ++d) mx = fmaxf(mx, fmaxf(__uint_as_float(v[d] << 16), __uint_as_float(v[d] & 0xFFFF0000u)));
+                        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xF, 0xF, false)));    // quad_perm [1,0,3,2]
+                        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xF, 0xF, false)));    // quad_perm [2,3,0,1]
+                        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xF, 0xF, false)));   // row_half_mirror
+                        rm[i][q] = fmaxf(rm[i][q], mx);
+                    }
                     if constexpr (LOADS_FIRST) {
                         if constexpr (decltype(idx)::value == 0 && q == 0) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
                         store16_untracked(dst, v, stream);
@@ -412,6 +446,32 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
                 });
                 __builtin_amdgcn_wave_barrier();
             });
+            if constexpr (EPI == EPI_ROWMAX) {
+                // The WN waves of one wave row hold maxima of the same TM rows over different columns:
+                // publish them in the (now idle) windows, one workgroup barrier, then the first wave
+                // of every wave row combines them and issues one atomic per row (a quarter of the
+                // atomics a wave-by-wave update would need).  The windows are next written in the
+                // next tile's epilogue, several barriers of the reduction loop later.
+                constexpr int WN_ = BN / TN;
+                float* win = reinterpret_cast<float*>(stage + wave * STAGE_BYTES);
+                if ((lane & 7) == 0) {
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) win[i * 32 + q * 8 + (lane >> 3)] = rm[i][q];
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (wn == 0) {
+#pragma unroll
+                    for (int t = 0; t < TM / 64; ++t) {
+                        const int row = lane + 64 * t;
+                        float mx = win[row];
+#pragma unroll
+                        for (int w = 1; w < WN_; ++w) mx = fmaxf(mx, reinterpret_cast<const float*>(stage + (wave + w) * STAGE_BYTES)[row]);
+                        atomic_max_f32_untracked(s.rowmax + (m0 + wm * TM + row), mx);
+                    }
+                }
+            }
         }
         return;
     }
@@ -428,6 +488,7 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
             if (m < s.m && n < s.n) {
                 if constexpr (LOADS_FIRST) store_out_untracked(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
                 else store_out(cp, (int64_t)(8 * (r >> 2) + (r & 3)) * s.ldc, v);
+                if constexpr (EPI == EPI_ROWMAX) atomic_max_f32_untracked(s.rowmax + m, bf16_to_f32(f32_to_bf16(v)));
             }
         });
     });
@@ -1183,6 +1244,9 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         max_m = plan.s[g].m > max_m ? plan.s[g].m : max_m;
         max_n = plan.s[g].n > max_n ? plan.s[g].n : max_n;
     }
+    // the fused row maximum exists in the persistent bf16 kernel only; the caller does anything else in two passes
+    if (plan.epilogue == EPI_ROWMAX && (max_m == 0 || max_n == 0 || plan.f32_operand || variant == 1 || !mfma_ok(plan)))
+        return SBP_ERR_UNSUPPORTED;
     if (max_m == 0 || max_n == 0) return SBP_OK;   // every local product is empty
 
     if (plan.f32_operand) {
@@ -1216,6 +1280,14 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
     bool k128 = true;   // every local reduction a whole number of four-stage rounds
     for (int g = 0; g < plan.groups; ++g)
         if (plan.s[g].m && plan.s[g].n && plan.s[g].kk % 128) k128 = false;
+    if (plan.epilogue == EPI_ROWMAX) {
+        // fused row maximum: persistent bf16 kernel only; anything else is done in two passes by the caller
+        if (!(k128 && max_m > 128 && max_n > 128 && plan.out_dtype == SBP_BF16 && (variant == 0 || variant == 12))) return SBP_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(fill_rowmax_kernel, dim3((uint32_t)((max_m + 255) / 256), (uint32_t)plan.groups), dim3(256), 0, stream, plan);
+        const int32_t st = launch_status(__func__);
+        if (st != SBP_OK) return st;
+        return launch_mfma_layout<256, 256, 2, 4, 104, EPI_ROWMAX, uint16_t>(plan, max_m, max_n, stream);
+    }
     if (variant == 0) {
         // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages, as one persistent
         // workgroup per compute unit when the reduction length allows it; shapes that would leave most

@@ -159,8 +159,9 @@ int32_t sbp_local_shape(int64_t rows, int64_t cols, sbp_t s, int32_t k, int32_t 
     return SBP_OK;
 }
 
-int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,
-                      sbp_t sy, int32_t k, void* stream, int32_t epilogue) {
+// rowmax != nullptr: also reduce every stored row over the local columns into rowmax (P(max), [M,1] f32)
+static int32_t matmul_impl(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,
+                           sbp_t sy, int32_t k, void* stream, int32_t epilogue, const sbp_tensor_t* rowmax) {
     if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
     if (!x || !w || !y) return SBP_ERR_NULL;
     if (!is_sbp(sx) || !is_sbp(sw)) return SBP_ERR_AXIS;
@@ -196,6 +197,20 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sb
     spans_of(w, sw, k, ins);
     spans_of(y, sy, k, outs);
     // a B output written k times to one buffer would be k writers of the same bytes: refuse it too
+    if (rowmax) {
+        if (sy != SBP_S(1)) return SBP_ERR_SIGNATURE;   // only a column-split result has partial row maxima
+        if (epilogue != SBP_EPI_NONE) return SBP_ERR_UNSUPPORTED;
+        if (!rowmax->shard) return SBP_ERR_NULL;
+        if (rowmax->rows != y->rows || rowmax->cols != 1) return SBP_ERR_SHAPE;
+        if (rowmax->dtype != SBP_F32) return SBP_ERR_DTYPE;
+        if (rowmax->trans) return SBP_ERR_UNSUPPORTED;
+        for (int32_t i = 0; i < k && y->rows > 0; ++i) {
+            if (!rowmax->shard[i]) return SBP_ERR_NULL;
+            if (reinterpret_cast<uintptr_t>(rowmax->shard[i]) & 15u) return SBP_ERR_ALIGN;
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(rowmax->shard[i]);
+            outs.push_back({lo, lo + (uintptr_t)y->rows * 4});
+        }
+    }
     if ((st = check_alias(outs, ins)) != SBP_OK) return st;
 
     GemmPlan plan{};
@@ -221,8 +236,37 @@ int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sb
         g.lda = (int32_t)(x->trans ? lx.rows : lx.cols);
         g.ldb = (int32_t)(w->trans ? lw.rows : lw.cols);
         g.ldc = (int32_t)ly.cols;
+        g.rowmax = rowmax ? static_cast<float*>(rowmax->shard[i]) : nullptr;
     }
-    return launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
+    if (!rowmax) return launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
+    // fused where the kernel has it, else the product followed by the row reduction
+    plan.epilogue = EPI_ROWMAX;
+    st = launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
+    if (st != SBP_ERR_UNSUPPORTED) return st;
+    plan.epilogue = SBP_EPI_NONE;
+    if ((st = launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream))) != SBP_OK) return st;
+    RowStatPlan rs{};
+    rs.rows = y->rows;
+    rs.k = k;
+    rs.dtype = y->dtype;
+    for (int32_t i = 0; i < k; ++i) {
+        rs.logits[i] = y->shard[i];
+        rs.gmax[i] = nullptr;
+        rs.out[i] = static_cast<float*>(rowmax->shard[i]);
+        rs.cols[i] = (int32_t)local_of(y->rows, y->cols, sy, k, i).cols;
+    }
+    return launch_row_stat(rs, false, static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_matmul_ex(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,
+                      sbp_t sy, int32_t k, void* stream, int32_t epilogue) {
+    return matmul_impl(x, sx, w, sw, y, sy, k, stream, epilogue, nullptr);
+}
+
+int32_t sbp_matmul_rowmax(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,
+                          sbp_t sy, const sbp_tensor_t* rowmax, int32_t k, void* stream) {
+    if (!rowmax) return SBP_ERR_NULL;
+    return matmul_impl(x, sx, w, sw, y, sy, k, stream, SBP_EPI_NONE, rowmax);
 }
 
 int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t sw, const sbp_tensor_t* y,

@@ -57,9 +57,12 @@ struct GemmShard {
     const void* a;
     const void* b;
     void* c;
+    float* rowmax;   // EPI_ROWMAX only: [m] fp32, max over this shard's columns of the stored results
     int32_t m, n, kk;
     int32_t lda, ldb, ldc;
 };
+// internal epilogue code next to the public SBP_EPI_*: store, and fold every stored row into rowmax
+constexpr int32_t EPI_ROWMAX = 2;
 struct GemmPlan {
     GemmShard s[SBP_MAX_K];
     int32_t groups;

@@ -556,3 +556,36 @@ def test_model_parallel_sparse_cross_entropy(k, cols, dtype):
         assert np.all(np.abs(gv - plain_g[i]) <= 2 * tol * np.abs(plain_g[i]) + 1e-7), f"gradient shard {i} vs plain"
         if gv.size:
             assert np.all(gv[3] == 0.0) and np.all(gv[7] == 0.0)
+
+
+@pytest.mark.parametrize("shape,k", [((1000, 256, 3 * 1304), 3), ((300, 128, 2 * 520), 2), ((45, 100, 3 * 17), 3), ((64, 64, 8 * 16), 8)])
+def test_matmul_with_fused_row_max(shape, k):
+    """sbp_matmul_rowmax: (B, S(1)) -> S(1) bf16 logits plus their local row maxima (P(max)) in one
+    call.  The first two shapes take the persistent kernel with the maximum folded into its stores
+    (several tiles per workgroup, ragged right and bottom edges), the others the two-pass form.  The
+    logits must be bit-identical to sbp_matmul's and the maxima bit-identical to sbp_row_max of them;
+    both are then checked against the oracle."""
+    M, K, N = shape
+    X, W = rnd_bf16(21, (M, K)), rnd_bf16(22, (K, N), 0.05)
+    X[5, :] = 0                                  # a row of zero logits (+0 / -0 products)
+    W[:, 7] = np.uint16(0x8000)                  # a column of -0
+    Xs, Ws = orc.scatter(X, orc.B, k), orc.scatter(W, orc.S1, k)
+    dx, dw = DevTensor.from_host(Xs, M, K, orc.B), DevTensor.from_host(Ws, K, N, orc.S1)
+    y_plain = DevTensor.empty(M, N, np.uint16, orc.S1, k)
+    y_fused = DevTensor.empty(M, N, np.uint16, orc.S1, k)
+    m_sep, m_fused = DevTensor.empty(M, 1, np.float32, orc.P_MAX, k), DevTensor.empty(M, 1, np.float32, orc.P_MAX, k)
+    sbp.sbp_matmul(dx.desc, sbp.B, dw.desc, sbp.S(1), y_plain.desc, sbp.S(1), k)
+    sbp.sbp_row_max(y_plain.desc, sbp.S(1), m_sep.desc, k)
+    sbp.sbp_matmul_rowmax(dx.desc, sbp.B, dw.desc, sbp.S(1), y_fused.desc, sbp.AUTO, m_fused.desc, k)
+    sync()
+    ref, _ = orc.matmul_sbp([values(x) for x in Xs], orc.B, [values(w) for w in Ws], orc.S1)
+    for i in range(k):
+        assert_bits_equal(y_fused.host()[i], y_plain.host()[i], f"logits shard {i}")
+        assert_matmul_close(values(y_fused.host()[i]), ref[i], 2e-2, f"logits shard {i} vs oracle")
+        got_m, sep_m = m_fused.host()[i][:, 0], m_sep.host()[i][:, 0]
+        assert np.array_equal(got_m, sep_m), f"row max shard {i}: fused vs separate"     # values (+0 == -0)
+        assert np.array_equal(got_m.astype(np.float64), orc.row_max(values(y_fused.host()[i]))), f"row max shard {i} vs oracle"
+    with pytest.raises(sbp.SbpError):           # a row-split result has no partial row maxima
+        sbp.sbp_matmul_rowmax(DevTensor.from_host(orc.scatter(X, orc.S0, k), M, K, orc.S0).desc, sbp.S(0),
+                              DevTensor.from_host(orc.scatter(W, orc.B, k), K, N, orc.B).desc, sbp.B,
+                              DevTensor.empty(M, N, np.uint16, orc.S0, k).desc, sbp.AUTO, m_fused.desc, k)
