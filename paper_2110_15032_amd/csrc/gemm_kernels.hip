@@ -1,11 +1,16 @@
 // Grouped per-shard GEMM for sbp_matmul (paper Sec. 3.1, Table 1): device g computes
 // C_g = A_g B_g from the local tensors it holds; all k devices run in ONE launch.
 //
-//   gemm_generic_kernel   any dtype / shape / pitch, one output element per lane, fp32 FMA chain.
-//                         Used for fp32 operands and for shapes the MFMA path does not take.
-//   gemm_mfma_kernel      bf16 x bf16 -> fp32 on the matrix cores (v_mfma_f32_32x32x16_bf16),
-//                         BM x BN x 64 macro-tile per workgroup, global->LDS loads that bypass
-//                         registers, double-buffered LDS.
+//   gemm_generic_kernel       any dtype / shape / pitch, one output element per lane, fp32 FMA chain.
+//                             Used for fp32 operands and for shapes the MFMA kernels do not take.
+//   gemm_mfma_kernel          bf16 x bf16 -> fp32 on the matrix cores (v_mfma_f32_32x32x16_bf16),
+//                             BM x BN macro-tile per workgroup, global->LDS loads that bypass
+//                             registers, two LDS stages of 64 reduction elements.
+//   gemm_mfma_pipe_kernel     the same with 3-5 stages of 32 and partial waits on the load counter.
+//   gemm_mfma_persist_kernel  four stages, one workgroup per compute unit walking many tiles, the next
+//                             tile's loads in flight across the epilogue: the default for large shapes.
+//   gemm_split_kernel         one fp32 operand (a P(sum) partial) split exactly into three bf16 terms.
+// All MFMA kernels share Tile (LDS images, swizzles, fragment reads) and store_tile (epilogue).
 //
 // Operand storage: "KC" = reduction index contiguous ([m][kk] for A, [n][kk] for B), otherwise the
 // reduction index is the slow one ([kk][m], [kk][n]).  Row-major X and W give A KC and B not-KC.
@@ -782,12 +787,14 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN <= 256 * 128 && WM * WN == 4
 // cannot start before the old one's stores have drained) nor the output stores themselves stop the
 // matrix pipe for longer than it takes to ISSUE the stores.
 //
-// In-order vmcnt bookkeeping: step g issues the loads of stage g + NST - 1 and needs stage g + 1.
-// After an epilogue the store instructions of this wave sit between those two in the queue, so the
-// first NST - 2 steps of the next tile may leave up to (NST - 2) NVM + (stores) operations
-// outstanding; the counter saturates at 63, which is a valid (stricter) bound as long as the epilogue
-// issued at least 63 - (NST - 2) NVM stores per wave -- true for interior tiles (16 FM FN of them).
-// After an edge tile (guarded, fewer stores) everything is drained once instead.
+// Memory-counter bookkeeping (loads and stores complete in issue order on one counter; every wait in
+// this kernel is explicit, its loads and stores being issued outside the compiler's own accounting):
+//   * a normal step issues the loads of the stage three ahead, then waits until at most the two
+//     youngest stages are outstanding, which means the stage it reads next has landed;
+//   * the epilogue waits for everything once, right before its first store, when the only things in
+//     flight are the next tile's stages 1 and 2, issued one and two steps earlier;
+//   * the first two steps of the next tile therefore need no wait at all, and the stores drain
+//     underneath them; the third step's "all but the two youngest stages" covers the stores too.
 // Requires every shard's reduction extent to be a multiple of 32 NST.
 // ------------------------------------------------------------------------------------------------
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int NST, int EPI, typename OutT>
@@ -802,7 +809,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
     constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
     constexpr int WAIT_KEEP = (NST - 2) * NVM;
     static_assert(NST == 4, "written for four stages");
-    static_assert(16 * FM * FN >= 63 - WAIT_KEEP, "interior epilogue must issue enough stores for the saturated wait");
     __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
     __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
     __shared__ __attribute__((aligned(1024))) char sA2[TA::BYTES];
