@@ -183,6 +183,24 @@ def test_xent_validation_errors():
     del dl
 
 
+def test_sizes_beyond_the_kernels_index_range_are_refused_not_wrapped():
+    """the boxing kernels index with 32 bits; a tensor of 2^40 elements must come back as
+    SBP_ERR_UNSUPPORTED before anything is launched (made-up addresses, never dereferenced)"""
+    k = 2
+    big = 1 << 20
+    step = 1 << 44
+    a = sbp.SbpTensor([1 << 46, (1 << 46) + step], big, big, sbp.F32)
+    b = sbp.SbpTensor([1 << 48, (1 << 48) + step], big, big, sbp.F32)
+    st = 0
+    for si, so in [(sbp.P_SUM, sbp.B), (sbp.S(0), sbp.B), (sbp.S(0), sbp.S(1)), (sbp.B, sbp.P_SUM)]:
+        assert status_of(sbp.sbp_boxing, a, si, b, so, k, st) == -9, (si, so)
+    a16 = sbp.SbpTensor([1 << 46, (1 << 46) + step], big, big, sbp.BF16)
+    assert status_of(sbp.sbp_boxing_cast, a, sbp.S(0), sbp.SbpTensor([1 << 48, (1 << 48) + step], big, big, sbp.BF16), sbp.B, k, st) == -9
+    assert status_of(sbp.sbp_boxing_cast, a16, sbp.P_SUM, b, sbp.S(0), k, st) == -9
+    wide = sbp.SbpTensor([1 << 46, (1 << 46) + step], 8, (1 << 31) + 8, sbp.F32)
+    assert status_of(sbp.sbp_matmul, a, sbp.B, wide, sbp.B, wide, sbp.B, k, st) in (-3, -9)
+
+
 def test_row_stat_validation_errors():
     k = 4
     L = fake(k, 16, 64, sbp.BF16)
