@@ -20,7 +20,9 @@ invariant under every boxing, Table 2's closed forms, numpy float64 matmul on
 the k = 1 case, torch's fp32->bf16 cast, the Table 4 program and the U.V.W
 deferred-boxing example; for the two-dimensional signatures of Sec. 3.3, Table 3
 as printed plus a brute-force derivation of every valid 2-D MatMul pair, and
-the reassembly invariant of boxing along either grid axis.  Parity unpinned by the paper (fixed by a stated
+the reassembly invariant of boxing along either grid axis; for boxing between
+disjoint placements, Table 2's other column, the reassembly invariant and the
+same-placement routine at k_in = k_out.  Parity unpinned by the paper (fixed by a stated
 reading only): the uneven-split rule, the GeLU variant, and which sign a
 P(max) of +0 and -0 yields.
 """
@@ -359,6 +361,79 @@ def transfer_elems(sbp_in, sbp_out, rows: int, cols: int, k: int) -> int:
                     moved += 0           # own copy
                 else:                    # P: one contribution per device, own one is local
                     moved += k - 1
+    return moved
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.2, Table 2, column "disjoint": the input lives on k_in devices and the
+# output on k_out OTHER devices, so every value the output holds has to travel.
+# ----------------------------------------------------------------------------
+def boxing_across(shards: list[np.ndarray], sbp_in, sbp_out, k_out: int) -> list[np.ndarray]:
+    """Boxing from a placement of k_in = len(shards) devices to a disjoint one of
+    k_out devices.  The global tensor is unchanged, so S and B outputs are
+    scatter(assemble(.)) with the output's own device count.  For a P output the
+    paper only prices the move (Table 2); the readings below are the ones that
+    move exactly the priced amount (parity unpinned by the paper):
+      S(a) -> P: output device j receives slice j of the balanced split of axis a
+                 over k_out devices and pads with the identity        (|T| moves)
+      B    -> P: output device 0 receives one copy, the rest hold the identity
+                                                                      (|T| moves)
+      P    -> P: partial i goes, whole, to output device i mod k_out; a device
+                 that receives several combines them in input order, one that
+                 receives none holds the identity                (k_in |T| move)"""
+    k_in = len(shards)
+    if sbp_out in (P_SUM, P_MAX):
+        ident = 0.0 if sbp_out == P_SUM else -np.inf
+        comb = np.add if sbp_out == P_SUM else np.maximum
+        if sbp_in in (P_SUM, P_MAX):
+            if sbp_in != sbp_out:
+                raise ValueError(f"boxing {sbp_in} -> {sbp_out} changes the reduction")
+            out = [None] * k_out
+            for i in range(k_in):
+                j = i % k_out
+                out[j] = _f64(shards[i]).copy() if out[j] is None else comb(out[j], _f64(shards[i]))
+            return [np.full(shards[0].shape, ident, dtype=np.float64) if o is None else o for o in out]
+        G = _f64(assemble(shards, sbp_in))
+        rows, cols = G.shape
+        out = [np.full((rows, cols), ident, dtype=np.float64) for _ in range(k_out)]
+        if sbp_in == B:
+            out[0][:, :] = G
+            return out
+        for j in range(k_out):
+            if sbp_in == S0:
+                b, e = split_range(rows, k_out, j)
+                out[j][b:e, :] = G[b:e, :]
+            else:
+                b, e = split_range(cols, k_out, j)
+                out[j][:, b:e] = G[:, b:e]
+        return out
+    return scatter(assemble(shards, sbp_in), sbp_out, k_out)
+
+
+def transfer_elems_across(sbp_in, k_in: int, sbp_out, k_out: int, rows: int, cols: int) -> int:
+    """Elements that travel when boxing between DISJOINT device sets, counted by
+    walking a routing: for every output device and every position where it ends
+    up holding a real value (not the padding identity of a P output), count the
+    contributions it receives; nothing is local.  P -> B is routed as Table 2
+    prices it: P -> S(0) onto the k_out output devices, then S(0) -> B among
+    them (there only the k_out - 1 other devices need each slice)."""
+    T = rows * cols
+    if sbp_in in (P_SUM, P_MAX) and sbp_out == B:
+        inner = transfer_elems(S0, B, rows, cols, k_out)
+        return transfer_elems_across(sbp_in, k_in, S0, k_out, rows, cols) + inner
+    if sbp_in in (P_SUM, P_MAX) and sbp_out in (P_SUM, P_MAX):
+        return k_in * T                                # partial i travels whole, once, to device i mod k_out
+    moved = 0
+    probe = np.arange(T, dtype=np.float64).reshape(rows, cols) + 1.0   # no zeros: padding is visible
+    held = boxing_across(scatter(probe, sbp_in, k_in) if sbp_in not in (P_SUM, P_MAX)
+                         else [probe] + [np.zeros_like(probe)] * (k_in - 1), sbp_in, sbp_out, k_out)
+    for j in range(k_out):
+        if sbp_out in (P_SUM, P_MAX):
+            real = int(np.count_nonzero(np.isfinite(held[j]) & (held[j] != 0)))
+        else:
+            real = held[j].size
+        per_value = k_in if sbp_in in (P_SUM, P_MAX) else 1   # a P value has one contribution per input device
+        moved += real * per_value
     return moved
 
 
