@@ -147,6 +147,25 @@ int32_t sbp_matmul_rowmax(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t
 int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out, sbp_t sbp_out,
                    int32_t k, void* stream);
 
+/* Boxing between DISJOINT placements (Sec. 3.2, Table 2, column "disjoint"): the input's local
+ * tensors live on k_in logical devices, the output's on k_out other ones; the global tensor is
+ * unchanged.  in->shard holds k_in pointers, out->shard k_out; the balanced split of an S
+ * signature uses its own side's device count.  Everything sbp_boxing states about dtypes,
+ * fp32 reductions in input order, raw-word moves, trans and aliasing holds here too.
+ *   S(a)/B/P -> S(b), B     out = scatter(assemble(in)) over k_out devices; from B every value
+ *                           is read from ONE copy (slice j from copy j mod k_in; B -> B from copy 0)
+ *   S(a) -> P(op)           out_j = slice j of the balanced split of axis a over the k_out devices,
+ *                           identity of op elsewhere            (every value travels once)
+ *   B -> P(op)              out_0 = a copy, the others hold the identity
+ *   P(op) -> P(op)          partial i goes whole to out_(i mod k_out); a device that receives
+ *                           several combines them in input order, one that receives none holds
+ *                           the identity                        (each partial travels once)
+ * With k_in == k_out every result equals sbp_boxing's.  The paper prices these moves but does not
+ * say where a P output's values land; the three P rows above are the placements that move exactly
+ * the priced amount. */
+int32_t sbp_boxing_across(const sbp_tensor_t* in, sbp_t sbp_in, int32_t k_in, const sbp_tensor_t* out,
+                          sbp_t sbp_out, int32_t k_out, void* stream);
+
 /* Precision cast fused into boxing (Sec. 6.4, sharded optimizer state with mixed
  * precision: the cast op's input is S(0) and its output B).
  *   forward:   in SBP_F32  S(a)    -> out SBP_BF16 B     out_j = bf16(concat_i in_i), every j;

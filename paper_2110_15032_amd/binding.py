@@ -28,7 +28,7 @@ KNOB_GEMM_VARIANT = 0
 KNOB_TILE_ORDER = 1
 
 #: every symbol include/sbp.h declares
-EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_matmul_rowmax", "sbp_boxing", "sbp_boxing_cast",
+EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_matmul_rowmax", "sbp_boxing", "sbp_boxing_across", "sbp_boxing_cast",
            "sbp_infer_matmul_2d", "sbp_local_shape_2d", "sbp_matmul_2d", "sbp_boxing_2d",
            "sbp_row_max", "sbp_row_sumexp", "sbp_xent_loss", "sbp_xent_grad", "sbp_set_knob", "sbp_strerror")
 
@@ -75,6 +75,7 @@ def lib() -> ctypes.CDLL:
         L.sbp_matmul_ex.argtypes = [T, i32, T, i32, T, i32, i32, vp, i32]
         L.sbp_matmul_rowmax.argtypes = [T, i32, T, i32, T, i32, T, i32, vp]
         L.sbp_boxing.argtypes = [T, i32, T, i32, i32, vp]
+        L.sbp_boxing_across.argtypes = [T, i32, i32, T, i32, i32, vp]
         L.sbp_boxing_cast.argtypes = [T, i32, T, i32, i32, vp]
         P2 = ctypes.POINTER(i32)
         L.sbp_infer_matmul_2d.argtypes = [P2, P2, P2]
@@ -160,6 +161,11 @@ def sbp_matmul_rowmax(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: Sbp
 
 def sbp_boxing(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
     _check(lib().sbp_boxing(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing")
+
+
+def sbp_boxing_across(inp: SbpTensor, sbp_in: int, k_in: int, out: SbpTensor, sbp_out: int, k_out: int, stream=None) -> None:
+    _check(lib().sbp_boxing_across(inp.ref(), sbp_in, k_in, out.ref(), sbp_out, k_out, _stream_ptr(stream)),
+           "sbp_boxing_across")
 
 
 def sbp_boxing_cast(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:

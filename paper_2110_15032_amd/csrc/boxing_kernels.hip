@@ -1,4 +1,7 @@
-// Boxing kernels (paper Sec. 3.2, Table 2, same device set), for k shard buffers in one HBM.
+// Boxing kernels (paper Sec. 3.2, Table 2), for shard buffers in one HBM: ki input devices, ko output
+// devices.  On one device set ki = ko = k (the table's "same" column); between disjoint placements
+// the two counts are independent (its "disjoint" column) and the task lists below generalise as
+// noted at make_task.
 //
 // Every conversion is a set of rectangle tasks (blockIdx.y = task).  A task reads one rows x cols
 // rectangle from NS source shards that all use the same offset and pitch, combines them in shard
@@ -13,7 +16,10 @@
 //   S(a) -> S(b)  k*k    : in_i restricted to slice j of b -> out_j at slice i   (all2all)
 //   B -> S(a)     k tasks: slice j of in_j (its own copy)  -> out_j              (local slice)
 //   X -> X        k tasks: in_i -> out_i                                         (identity)
-//   S(a), B -> P  own kernel (box_to_partial_kernel): own values kept, identity elsewhere
+//   S(a), B -> P  own kernels (box_to_partial*_kernel): own values kept, identity elsewhere
+//   ki != ko only: S(a) -> S(a) takes the all2all task list (ki*ko range intersections), B -> B is the
+//                  all-gather of a tensor "split" over one device, and
+//   P -> P        ko tasks: partials j, j + ko, j + 2 ko, ... combined in that order -> out_j
 //
 // HBM-bound: every input byte is read once and every output byte written once, with the widest
 // vector (up to 16 B per lane) that all offsets and pitches of the conversion allow.
@@ -24,13 +30,13 @@
 namespace sbp {
 namespace {
 
-enum BoxMode : int32_t { M_P2B = 0, M_P2S, M_S2B, M_S2S, M_B2S, M_IDENT };
+enum BoxMode : int32_t { M_P2B = 0, M_P2S, M_S2B, M_S2S, M_B2S, M_IDENT, M_P2P };
 
 struct BoxParams {
     const void* src[SBP_MAX_K];
     void* dst[SBP_MAX_K];
     int64_t rows, cols;   // global shape in elements
-    int32_t k;
+    int32_t ki, ko;       // input / output device count
     int32_t mode;
     int32_t axis_in;      // split axis of the input  (S inputs), else -1
     int32_t axis_out;     // split axis of the output (S outputs), else -1
@@ -39,10 +45,11 @@ struct BoxParams {
 };
 
 struct Task {
-    int32_t s0, ns;       // sources  [s0, s0 + ns)
-    int32_t d0, nd;       // destinations
+    int32_t s0, ns;       // sources  s0, s0 + sstep, ... (ns of them)
+    int32_t d0, nd;       // destinations [d0, d0 + nd)
     int64_t src_off, dst_off, src_ld, dst_ld;   // elements
     int64_t rows, cols;   // rectangle, elements
+    int32_t sstep;        // distance between consecutive sources (1 except P -> P)
 };
 
 __host__ __device__ inline void range_of(int64_t n, int32_t k, int32_t i, int32_t axis_is_split, int64_t& b, int64_t& l) {
@@ -58,50 +65,56 @@ __host__ __device__ inline void range_of(int64_t n, int32_t k, int32_t i, int32_
 // Geometry of task t.  Shared by the launcher (alignment analysis, grid sizing) and the kernel.
 __host__ __device__ inline Task make_task(const BoxParams& p, int32_t t) {
     Task T{};
-    const int32_t k = p.k;
+    const int32_t ki = p.ki, ko = p.ko;
     int64_t rb, rl, cb, cl;
     switch (p.mode) {
         case M_P2B:
-            T = {0, k, 0, k, 0, 0, p.cols, p.cols, p.rows, p.cols};
+            T = {0, ki, 0, ko, 0, 0, p.cols, p.cols, p.rows, p.cols};
             break;
         case M_P2S: {
-            range_of(p.rows, k, t, p.axis_out == 0, rb, rl);
-            range_of(p.cols, k, t, p.axis_out == 1, cb, cl);
-            T = {0, k, t, 1, rb * p.cols + cb, 0, p.cols, cl, rl, cl};
+            range_of(p.rows, ko, t, p.axis_out == 0, rb, rl);
+            range_of(p.cols, ko, t, p.axis_out == 1, cb, cl);
+            T = {0, ki, t, 1, rb * p.cols + cb, 0, p.cols, cl, rl, cl};
             break;
         }
         case M_S2B: {
-            range_of(p.rows, k, t, p.axis_in == 0, rb, rl);
-            range_of(p.cols, k, t, p.axis_in == 1, cb, cl);
-            T = {t, 1, 0, k, 0, rb * p.cols + cb, cl, p.cols, rl, cl};
+            range_of(p.rows, ki, t, p.axis_in == 0, rb, rl);
+            range_of(p.cols, ki, t, p.axis_in == 1, cb, cl);
+            T = {t, 1, 0, ko, 0, rb * p.cols + cb, cl, p.cols, rl, cl};
             break;
         }
         case M_S2S: {
-            const int32_t i = t / k, j = t % k;   // in_i -> out_j, axis_in != axis_out
+            const int32_t i = t / ko, j = t % ko;   // in_i -> out_j
             int64_t irb, irl, icb, icl, orb, orl, ocb, ocl;
-            range_of(p.rows, k, i, p.axis_in == 0, irb, irl);
-            range_of(p.cols, k, i, p.axis_in == 1, icb, icl);
-            range_of(p.rows, k, j, p.axis_out == 0, orb, orl);
-            range_of(p.cols, k, j, p.axis_out == 1, ocb, ocl);
-            // intersection in global coordinates: one side is split by rows, the other by columns
+            range_of(p.rows, ki, i, p.axis_in == 0, irb, irl);
+            range_of(p.cols, ki, i, p.axis_in == 1, icb, icl);
+            range_of(p.rows, ko, j, p.axis_out == 0, orb, orl);
+            range_of(p.cols, ko, j, p.axis_out == 1, ocb, ocl);
+            // intersection in global coordinates (empty for most pairs when both sides split the same axis)
             const int64_t r0 = irb > orb ? irb : orb, r1 = (irb + irl) < (orb + orl) ? (irb + irl) : (orb + orl);
             const int64_t c0 = icb > ocb ? icb : ocb, c1 = (icb + icl) < (ocb + ocl) ? (icb + icl) : (ocb + ocl);
-            T = {i, 1, j, 1, (r0 - irb) * icl + (c0 - icb), (r0 - orb) * ocl + (c0 - ocb), icl, ocl, r1 - r0, c1 - c0};
+            T = {i, 1, j, 1, (r0 - irb) * icl + (c0 - icb), (r0 - orb) * ocl + (c0 - ocb), icl, ocl,
+                 r1 > r0 ? r1 - r0 : 0, c1 > c0 ? c1 - c0 : 0};
             break;
         }
-        case M_B2S: {
-            range_of(p.rows, k, t, p.axis_out == 0, rb, rl);
-            range_of(p.cols, k, t, p.axis_out == 1, cb, cl);
-            T = {t, 1, t, 1, rb * p.cols + cb, 0, p.cols, cl, rl, cl};
+        case M_B2S: {   // device t takes its slice from a copy on "its" input device (its own when ki == ko)
+            range_of(p.rows, ko, t, p.axis_out == 0, rb, rl);
+            range_of(p.cols, ko, t, p.axis_out == 1, cb, cl);
+            T = {t % ki, 1, t, 1, rb * p.cols + cb, 0, p.cols, cl, rl, cl};
             break;
         }
-        default: {  // M_IDENT
-            range_of(p.rows, k, t, p.sbp_same == 0, rb, rl);
-            range_of(p.cols, k, t, p.sbp_same == 1, cb, cl);
+        case M_P2P: {   // partials t, t + ko, ... -> out_t; none when t >= ki (the kernel then writes the identity)
+            T = {t, t < ki ? (ki - t + ko - 1) / ko : 0, t, 1, 0, 0, p.cols, p.cols, p.rows, p.cols};
+            break;
+        }
+        default: {  // M_IDENT (ki == ko)
+            range_of(p.rows, ki, t, p.sbp_same == 0, rb, rl);
+            range_of(p.cols, ki, t, p.sbp_same == 1, cb, cl);
             T = {t, 1, t, 1, 0, 0, cl, cl, rl, cl};
             break;
         }
     }
+    T.sstep = p.mode == M_P2P ? ko : 1;
     // A rectangle as wide as both pitches is one contiguous run: flatten it so the kernel's
     // row / column split degenerates (no division on the hot path).
     if (T.cols == T.src_ld && T.cols == T.dst_ld) {
@@ -148,16 +161,20 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
                 const uint32_t c = idx - r * cols_v;
                 const int64_t spos = src_off_v + (int64_t)r * src_ld_v + c;
                 dpos[u] = dst_off_v + (int64_t)r * dst_ld_v + c;
-                V a = __builtin_nontemporal_load(static_cast<const V*>(p.src[0]) + spos);
-                if constexpr (KS > 0) {
+                V a;
+                if constexpr (KS > 0) {   // sources 0 .. KS-1
+                    a = __builtin_nontemporal_load(static_cast<const V*>(p.src[0]) + spos);
                     V part[KS];
 #pragma unroll
                     for (int i = 1; i < KS; ++i) part[i] = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos);
 #pragma unroll
                     for (int i = 1; i < KS; ++i) a = combine<OP>(a, part[i]);
                 } else {
+                    if constexpr (OP == BOX_SUM) a = V(0.0f);
+                    else a = V(-__builtin_inff());
+                    if (ns > 0) a = __builtin_nontemporal_load(static_cast<const V*>(p.src[T.s0]) + spos);
                     for (int i = 1; i < ns; ++i) {
-                        const V b = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos);
+                        const V b = __builtin_nontemporal_load(static_cast<const V*>(p.src[T.s0 + i * T.sstep]) + spos);
                         a = combine<OP>(a, b);
                     }
                 }
@@ -226,9 +243,9 @@ template <typename V>
 __global__ __launch_bounds__(BOX_THREADS) void box_gather_bcast_kernel(BoxParams p, uint32_t log2_pieces, uint32_t total,
                                                                         uint32_t q, uint32_t rem) {
     __shared__ const V* sp[SBP_MAX_K];
-    if ((int)threadIdx.x < p.k) sp[threadIdx.x] = static_cast<const V*>(p.src[threadIdx.x]);
+    if ((int)threadIdx.x < p.ki) sp[threadIdx.x] = static_cast<const V*>(p.src[threadIdx.x]);
     __syncthreads();
-    const uint32_t k = (uint32_t)p.k;
+    const uint32_t k = (uint32_t)p.ko;
     const uint32_t piece = blockIdx.x & ((1u << log2_pieces) - 1);
     const uint32_t cj = blockIdx.x >> log2_pieces;
     const uint32_t chunk = cj / k, j = cj - chunk * k;
@@ -307,9 +324,9 @@ template <int VE>
 __global__ __launch_bounds__(BOX_THREADS) void box_cast_gather_kernel(BoxParams p, uint32_t log2_pieces, uint32_t total,
                                                                        uint32_t q, uint32_t rem) {
     __shared__ const float* sp[SBP_MAX_K];
-    if ((int)threadIdx.x < p.k) sp[threadIdx.x] = static_cast<const float*>(p.src[threadIdx.x]);
+    if ((int)threadIdx.x < p.ki) sp[threadIdx.x] = static_cast<const float*>(p.src[threadIdx.x]);
     __syncthreads();
-    const uint32_t k = (uint32_t)p.k;
+    const uint32_t k = (uint32_t)p.ko;
     const uint32_t piece = blockIdx.x & ((1u << log2_pieces) - 1);
     const uint32_t cj = blockIdx.x >> log2_pieces;
     const uint32_t chunk = cj / k, j = cj - chunk * k;
@@ -396,8 +413,8 @@ __global__ __launch_bounds__(BOX_THREADS) void box_to_partial_kernel(BoxParams p
     const uint32_t lv = __builtin_ctz((uint32_t)p.vec_elems);
     const uint32_t cols_v = (uint32_t)(p.cols >> lv);
     int64_t rb = 0, rl = p.rows, cb = 0, cl = p.cols;
-    if (p.axis_in == 0) range_of(p.rows, p.k, j, 1, rb, rl);
-    if (p.axis_in == 1) range_of(p.cols, p.k, j, 1, cb, cl);
+    if (p.axis_in == 0) range_of(p.rows, p.ko, j, 1, rb, rl);
+    if (p.axis_in == 1) range_of(p.cols, p.ko, j, 1, cb, cl);
     if (p.axis_in < 0 && j > 0) rl = 0;   // B: only device 0 contributes
     const V* __restrict__ src = static_cast<const V*>(p.src[j]);
     V* __restrict__ dst = static_cast<V*>(p.dst[j]);
@@ -415,10 +432,58 @@ __global__ __launch_bounds__(BOX_THREADS) void box_to_partial_kernel(BoxParams p
     }
 }
 
+// S(a) -> P(op) between placements of different size: output device j receives slice j of the balanced
+// split of axis a over the ko OUTPUT devices (every value travels once, the table's price), so a
+// position inside that slice is fetched from whichever of the ki input shards owns it.
+template <typename V, bool MAXOP>
+__global__ __launch_bounds__(BOX_THREADS) void box_to_partial_across_kernel(BoxParams p, uint32_t total) {
+    __shared__ const V* sp[SBP_MAX_K];
+    if ((int)threadIdx.x < p.ki) sp[threadIdx.x] = static_cast<const V*>(p.src[threadIdx.x]);
+    __syncthreads();
+    const int32_t j = blockIdx.y;
+    const uint32_t lv = __builtin_ctz((uint32_t)p.vec_elems);
+    const uint32_t cols_v = (uint32_t)(p.cols >> lv);
+    const bool by_rows = p.axis_in == 0;
+    const uint32_t n = (uint32_t)(by_rows ? p.rows : p.cols);
+    const uint32_t ob = (uint32_t)split_begin(n, p.ko, j), ol = (uint32_t)split_len(n, p.ko, j);   // this device's slice
+    const uint32_t q = n / (uint32_t)p.ki, rem = n % (uint32_t)p.ki, edge = rem * (q + 1);        // the input's split
+    V* __restrict__ dst = static_cast<V*>(p.dst[j]);
+    V ident;
+    if constexpr (MAXOP) ident = V(-__builtin_inff());
+    else ident = V(0.0f);
+    const uint32_t stride = gridDim.x * BOX_THREADS;
+    for (uint32_t idx = blockIdx.x * BOX_THREADS + threadIdx.x; idx < total; idx += stride) {
+        const uint32_t r = idx / cols_v, c = idx - r * cols_v;
+        const uint32_t x = by_rows ? r : c << lv;
+        V v = ident;
+        if (x - ob < ol) {   // unsigned: ob <= x < ob + ol
+            uint32_t i, begin, len;
+            if (x < edge) {
+                i = x / (q + 1);
+                begin = i * (q + 1);
+                len = q + 1;
+            } else {
+                i = (x - edge) / q;   // q > 0 here: with q == 0 every index lies below edge
+                begin = edge + i * q;
+                i += rem;
+                len = q;
+            }
+            const int64_t spos = by_rows ? ((int64_t)(r - begin) * p.cols + ((int64_t)c << lv)) : ((int64_t)r * len + (x - begin));
+            v = __builtin_nontemporal_load(sp[i] + (spos >> lv));
+        }
+        __builtin_nontemporal_store(v, dst + idx);
+    }
+}
+
 template <typename V>
-void launch_to_partial(const BoxParams& p, bool maxop, dim3 grid, uint32_t total, hipStream_t st) {
-    if (maxop) hipLaunchKernelGGL((box_to_partial_kernel<V, true>), grid, dim3(BOX_THREADS), 0, st, p, total);
-    else hipLaunchKernelGGL((box_to_partial_kernel<V, false>), grid, dim3(BOX_THREADS), 0, st, p, total);
+void launch_to_partial(const BoxParams& p, bool maxop, bool across, dim3 grid, uint32_t total, hipStream_t st) {
+    if (across) {
+        if (maxop) hipLaunchKernelGGL((box_to_partial_across_kernel<V, true>), grid, dim3(BOX_THREADS), 0, st, p, total);
+        else hipLaunchKernelGGL((box_to_partial_across_kernel<V, false>), grid, dim3(BOX_THREADS), 0, st, p, total);
+    } else {
+        if (maxop) hipLaunchKernelGGL((box_to_partial_kernel<V, true>), grid, dim3(BOX_THREADS), 0, st, p, total);
+        else hipLaunchKernelGGL((box_to_partial_kernel<V, false>), grid, dim3(BOX_THREADS), 0, st, p, total);
+    }
 }
 
 inline int64_t gcd64(int64_t a, int64_t b) {
@@ -432,7 +497,7 @@ inline int64_t gcd64(int64_t a, int64_t b) {
 
 template <typename V, int OP, int UNROLL>
 void launch_reduce_k(const BoxParams& p, dim3 grid, hipStream_t st) {
-    switch (p.k) {
+    switch (p.mode == M_P2P ? 0 : p.ki) {   // P -> P walks a strided source list: run-time count
         case 2: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 2, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
         case 4: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 4, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
         case 8: hipLaunchKernelGGL((box_reduce_kernel<V, OP, 8, UNROLL>), grid, dim3(BOX_THREADS), 0, st, p); break;
@@ -463,58 +528,74 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     BoxParams p{};
     p.rows = plan.rows;
     p.cols = plan.cols;
-    p.k = plan.k;
+    p.ki = plan.k;
+    p.ko = plan.k_out;
+    const int32_t ki = plan.k, ko = plan.k_out;
     p.axis_in = (plan.sbp_in == SBP_S(0) || plan.sbp_in == SBP_S(1)) ? plan.sbp_in : -1;
     p.axis_out = (plan.sbp_out == SBP_S(0) || plan.sbp_out == SBP_S(1)) ? plan.sbp_out : -1;
-    for (int i = 0; i < plan.k; ++i) {
-        p.src[i] = plan.src[i];
-        p.dst[i] = plan.dst[i];
-    }
+    for (int i = 0; i < ki; ++i) p.src[i] = plan.src[i];
+    for (int i = 0; i < ko; ++i) p.dst[i] = plan.dst[i];
     const bool p_in = plan.sbp_in == SBP_P_SUM || plan.sbp_in == SBP_P_MAX;
     const bool p_out = plan.sbp_out == SBP_P_SUM || plan.sbp_out == SBP_P_MAX;
     int32_t tasks;
-    if (plan.sbp_in == plan.sbp_out) {
+    if (plan.sbp_in == plan.sbp_out && ki == ko) {
         p.mode = M_IDENT;
         p.sbp_same = plan.sbp_in;
-        tasks = plan.k;
+        tasks = ki;
+    } else if (p_in && p_out) {
+        p.mode = M_P2P;
+        tasks = ko;
     } else if (p_out) {
         // S -> P, B -> P: own values kept, identity elsewhere
         if (plan.elem_bytes != 4) return SBP_ERR_DTYPE;
+        const bool across = ki != ko && p.axis_in >= 0;   // B -> P reads copy 0 only, whatever the counts
         int64_t g = 4;   // fp32 elements in 16 bytes
         g = gcd64(g, plan.cols);
-        if (p.axis_in == 1)
-            for (int32_t i = 0; i < plan.k; ++i) {
-                g = gcd64(g, split_begin(plan.cols, plan.k, i));
-                g = gcd64(g, split_len(plan.cols, plan.k, i));
+        if (p.axis_in == 1) {
+            for (int32_t i = 0; i < ki; ++i) {
+                g = gcd64(g, split_begin(plan.cols, ki, i));
+                g = gcd64(g, split_len(plan.cols, ki, i));
             }
+            for (int32_t i = 0; i < ko; ++i) {
+                g = gcd64(g, split_begin(plan.cols, ko, i));
+                g = gcd64(g, split_len(plan.cols, ko, i));
+            }
+        }
         const int64_t total_v = plan.rows * plan.cols / g;
         if (total_v == 0) return SBP_OK;
-        if (total_v >= ((int64_t)1 << 31)) return SBP_ERR_UNSUPPORTED;
+        if (total_v >= ((int64_t)1 << 31) || plan.rows >= ((int64_t)1 << 31) || plan.cols >= ((int64_t)1 << 31))
+            return SBP_ERR_UNSUPPORTED;
         p.vec_elems = (int32_t)g;
         int64_t bx = (total_v + BOX_THREADS - 1) / BOX_THREADS;
-        const int64_t cap = (131072 + plan.k - 1) / plan.k;
+        const int64_t cap = (131072 + ko - 1) / ko;
         if (bx > cap) bx = cap;
-        const dim3 grid((uint32_t)bx, (uint32_t)plan.k);
+        const dim3 grid((uint32_t)bx, (uint32_t)ko);
         const bool maxop = plan.sbp_out == SBP_P_MAX;
-        if (g == 4) launch_to_partial<f32x4>(p, maxop, grid, (uint32_t)total_v, stream);
-        else if (g == 2) launch_to_partial<f32x2>(p, maxop, grid, (uint32_t)total_v, stream);
-        else launch_to_partial<float>(p, maxop, grid, (uint32_t)total_v, stream);
+        if (g == 4) launch_to_partial<f32x4>(p, maxop, across, grid, (uint32_t)total_v, stream);
+        else if (g == 2) launch_to_partial<f32x2>(p, maxop, across, grid, (uint32_t)total_v, stream);
+        else launch_to_partial<float>(p, maxop, across, grid, (uint32_t)total_v, stream);
         return launch_status(__func__);
     } else if (p_in && plan.sbp_out == SBP_B) {
         p.mode = M_P2B;
         tasks = 1;
     } else if (p_in) {
         p.mode = M_P2S;
-        tasks = plan.k;
+        tasks = ko;
+    } else if (plan.sbp_in == SBP_B && plan.sbp_out == SBP_B) {
+        // B -> B onto another device count: all-gather of a tensor "split" over one device (copy 0)
+        p.mode = M_S2B;
+        p.ki = 1;
+        p.axis_in = 0;
+        tasks = 1;
     } else if (plan.sbp_in == SBP_B) {
         p.mode = M_B2S;
-        tasks = plan.k;
+        tasks = ko;
     } else if (plan.sbp_out == SBP_B) {
         p.mode = M_S2B;
-        tasks = plan.k;
+        tasks = ki;
     } else {
-        p.mode = M_S2S;
-        tasks = plan.k * plan.k;
+        p.mode = M_S2S;   // also S(a) -> S(a) between different device counts
+        tasks = ki * ko;
     }
     if (tasks > 65535) return SBP_ERR_UNSUPPORTED;
 
@@ -539,21 +620,21 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     max_units /= g;
     if (max_units >= (int64_t)1 << 31) return SBP_ERR_UNSUPPORTED;
 
-    const bool reduce = p_in && plan.sbp_in != plan.sbp_out;
+    const bool reduce = p_in && p.mode != M_IDENT;
     const int vbytes = p.vec_elems * plan.elem_bytes;
     const int64_t total_v = plan.rows * plan.cols / g;
-    if (p.mode == M_S2B && plan.k > 1 && vbytes == 16 && plan.cols % g == 0 && total_v < ((int64_t)1 << 31) &&
+    if (p.mode == M_S2B && ko > 1 && vbytes == 16 && plan.cols % g == 0 && total_v < ((int64_t)1 << 31) &&
         plan.rows < ((int64_t)1 << 31) && plan.cols < ((int64_t)1 << 31)) {
         const int64_t per_piece = (int64_t)BOX_THREADS * BCAST_U;                 // 4 KB
         const int64_t need = (total_v + per_piece - 1) / per_piece;
         uint32_t lp = 3;                                                         // 8 .. 2048 pieces per chunk (8 MB)
         while (lp < 11 && ((int64_t)1 << lp) < need) ++lp;
         const int64_t chunks = (need + ((int64_t)1 << lp) - 1) >> lp;
-        const int64_t blocks = (chunks * plan.k) << lp;
+        const int64_t blocks = (chunks * ko) << lp;
         if (blocks < ((int64_t)1 << 31)) {
             const int64_t n = p.axis_in == 0 ? plan.rows : plan.cols;
             hipLaunchKernelGGL(box_gather_bcast_kernel<u32x4>, dim3((uint32_t)blocks), dim3(BOX_THREADS), 0, stream, p, lp,
-                               (uint32_t)total_v, (uint32_t)(n / plan.k), (uint32_t)(n % plan.k));
+                               (uint32_t)total_v, (uint32_t)(n / p.ki), (uint32_t)(n % p.ki));
             return launch_status(__func__);
         }
     }
@@ -584,7 +665,7 @@ int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream) {
     BoxParams p{};
     p.rows = plan.rows;
     p.cols = plan.cols;
-    p.k = plan.k;
+    p.ki = p.ko = plan.k;
     p.axis_in = (plan.sbp_in == SBP_S(0) || plan.sbp_in == SBP_S(1)) ? plan.sbp_in : -1;
     p.axis_out = (plan.sbp_out == SBP_S(0) || plan.sbp_out == SBP_S(1)) ? plan.sbp_out : -1;
     for (int i = 0; i < plan.k; ++i) {

@@ -275,13 +275,14 @@ int32_t sbp_matmul(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* w, sbp_t
 }
 
 // launch = false: every check, nothing enqueued (the 2-D entry validates all its 1-D parts first)
-static int32_t boxing_impl(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
-                           void* stream, bool launch) {
-    if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
+// k_in = k_out: one device set; otherwise two disjoint placements
+static int32_t boxing_impl(const sbp_tensor_t* in, sbp_t s_in, int32_t k_in, const sbp_tensor_t* out, sbp_t s_out,
+                           int32_t k_out, void* stream, bool launch) {
+    if (k_in < 1 || k_in > SBP_MAX_K || k_out < 1 || k_out > SBP_MAX_K) return SBP_ERR_K;
     if (!in || !out) return SBP_ERR_NULL;
     int32_t st;
-    if ((st = check_tensor(in, s_in, k)) != SBP_OK) return st;
-    if ((st = check_tensor(out, s_out, k)) != SBP_OK) return st;
+    if ((st = check_tensor(in, s_in, k_in)) != SBP_OK) return st;
+    if ((st = check_tensor(out, s_out, k_out)) != SBP_OK) return st;
     if (in->rows != out->rows || in->cols != out->cols) return SBP_ERR_SHAPE;
     if (in->dtype != out->dtype) return SBP_ERR_DTYPE;
     if ((is_partial(s_in) || is_partial(s_out)) && in->dtype != SBP_F32) return SBP_ERR_DTYPE;
@@ -289,27 +290,31 @@ static int32_t boxing_impl(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_
     if (is_partial(s_in) && is_partial(s_out) && s_in != s_out) return SBP_ERR_SIGNATURE;
 
     std::vector<Span> ins, outs;
-    spans_of(in, s_in, k, ins);
-    spans_of(out, s_out, k, outs);
+    spans_of(in, s_in, k_in, ins);
+    spans_of(out, s_out, k_out, outs);
     if ((st = check_alias(outs, ins)) != SBP_OK) return st;
 
     BoxPlan plan{};
     plan.rows = in->rows;
     plan.cols = in->cols;
-    plan.k = k;
+    plan.k = k_in;
+    plan.k_out = k_out;
     plan.sbp_in = s_in;
     plan.sbp_out = s_out;
     plan.elem_bytes = elem_bytes(in->dtype);
-    for (int32_t i = 0; i < k; ++i) {
-        plan.src[i] = in->shard[i];
-        plan.dst[i] = out->shard[i];
-    }
+    for (int32_t i = 0; i < k_in; ++i) plan.src[i] = in->shard[i];
+    for (int32_t i = 0; i < k_out; ++i) plan.dst[i] = out->shard[i];
     return launch ? launch_boxing(plan, static_cast<hipStream_t>(stream)) : SBP_OK;
 }
 
 int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
                    void* stream) {
-    return boxing_impl(in, s_in, out, s_out, k, stream, true);
+    return boxing_impl(in, s_in, k, out, s_out, k, stream, true);
+}
+
+int32_t sbp_boxing_across(const sbp_tensor_t* in, sbp_t s_in, int32_t k_in, const sbp_tensor_t* out, sbp_t s_out,
+                          int32_t k_out, void* stream) {
+    return boxing_impl(in, s_in, k_in, out, s_out, k_out, stream, true);
 }
 
 int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* out, sbp_t s_out, int32_t k,
@@ -335,7 +340,7 @@ int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t s_in, const sbp_tensor_t* 
     BoxPlan plan{};
     plan.rows = in->rows;
     plan.cols = in->cols;
-    plan.k = k;
+    plan.k = plan.k_out = k;
     plan.sbp_in = s_in;
     plan.sbp_out = s_out;
     plan.elem_bytes = 0;
@@ -476,7 +481,7 @@ int32_t sbp_boxing_2d(const sbp_tensor_t* in, const sbp_t* s_in, const sbp_tenso
     for (int pass = 0; pass < 2; ++pass)   // validate every part, then launch every part
         for (int32_t g = 0; g < parts; ++g) {
             if (tin[g].rows * tin[g].cols == 0) continue;
-            if ((st = boxing_impl(&tin[g], a, &tout[g], b, kk, stream, pass == 1)) != SBP_OK) return st;
+            if ((st = boxing_impl(&tin[g], a, kk, &tout[g], b, kk, stream, pass == 1)) != SBP_OK) return st;
         }
     return SBP_OK;
 }

@@ -39,7 +39,8 @@ struct BoxPlan {
     const void* src[SBP_MAX_K];
     void* dst[SBP_MAX_K];
     int64_t rows, cols;       // global shape, in elements
-    int32_t k;
+    int32_t k;                // devices holding the input
+    int32_t k_out;            // devices holding the output (= k on one device set; launch_boxing_cast ignores it)
     int32_t sbp_in, sbp_out;  // sbp_t values
     int32_t elem_bytes;       // 2 or 4
 };

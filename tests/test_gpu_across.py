@@ -1,0 +1,148 @@
+"""GPU parity for boxing between disjoint placements (Sec. 3.2, Table 2, column "disjoint"):
+sbp_boxing_across through the C ABI against the oracle, element by element.  Bars as for boxing on
+one device set: bit-exact for raw-word relayout, for P(max) and for values placed into partials;
+1e-5 * sum|in_i| for fp32 P(sum) reductions."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle as orc
+import paper_2110_15032_amd as sbp
+import workloads as wl
+from sbp_harness import DevTensor, TO_ABI, assert_bits_equal, assert_psum_close, sync
+
+pytestmark = pytest.mark.gpu
+SEED = wl.SEED_BASE + 77
+COUNTS = [(2, 3), (3, 2), (4, 4), (1, 5), (5, 1), (8, 16), (16, 8), (7, 3)]
+SHAPES = [(64, 96), (37, 53), (16, 1024), (130, 24), (5, 3), (240, 1680)]
+
+
+def rnd_f32(tid, shape):
+    return wl.normal(SEED, tid, shape).astype(np.float32)
+
+
+def rnd_words(tid, shape):
+    w = wl.uniform(SEED, tid, shape, 0.0, 65536.0).astype(np.uint32).astype(np.uint16)
+    w.flat[:4] = [0x7F80, 0x7FC1, 0xFF80, 0xFFFF][: min(4, w.size)]
+    return w
+
+
+def random_partials(tid, T, k, op):
+    if op == "sum":
+        parts = [rnd_f32(tid + 1 + i, T.shape) for i in range(k - 1)]
+        return parts + [(T - np.sum(parts, axis=0, dtype=np.float32)).astype(np.float32)]
+    return [(T - np.abs(rnd_f32(tid + 1 + i, T.shape)) * (i % 2)).astype(np.float32) for i in range(k)]
+
+
+def run(ins, si, k_in, so, k_out, shape, out_dtype):
+    print(f"across {si}->{so} k_in={k_in} k_out={k_out} shape={shape} dtype={np.dtype(out_dtype).name}", flush=True)
+    d_in = DevTensor.from_host(ins, *shape, si)
+    d_out = DevTensor.empty(*shape, out_dtype, so, k_out)
+    sbp.sbp_boxing_across(d_in.desc, TO_ABI[si], k_in, d_out.desc, TO_ABI[so], k_out)
+    sync()
+    return d_out.host()
+
+
+@pytest.mark.parametrize("k_in,k_out", COUNTS)
+@pytest.mark.parametrize("si,so", list(itertools.product((orc.S0, orc.S1, orc.B), repeat=2)))
+@pytest.mark.parametrize("words", ["u16", "f32"])
+def test_relayout_across_is_bit_exact(k_in, k_out, si, so, words):
+    for n, shape in enumerate(SHAPES):
+        T = rnd_words(n, shape) if words == "u16" else rnd_f32(n, shape)
+        ins = orc.scatter(T, si, k_in)
+        ref = orc.boxing_across(ins, si, so, k_out)
+        got = run(ins, si, k_in, so, k_out, shape, T.dtype)
+        assert len(got) == k_out
+        for j, (g, r) in enumerate(zip(got, ref)):
+            assert_bits_equal(g, r, f"{si}->{so} {k_in}->{k_out} shape={shape} shard {j}")
+
+
+@pytest.mark.parametrize("k_in,k_out", COUNTS)
+@pytest.mark.parametrize("op", ["sum", "max"])
+@pytest.mark.parametrize("so", [orc.B, orc.S0, orc.S1])
+def test_partial_value_boxing_across(k_in, k_out, op, so):
+    si = orc.P_SUM if op == "sum" else orc.P_MAX
+    for n, shape in enumerate(SHAPES):
+        T = rnd_f32(100 + n, shape)
+        parts = random_partials(200 + 20 * n, T, k_in, op)
+        ref = orc.boxing_across(parts, si, so, k_out)           # float64
+        got = run(parts, si, k_in, so, k_out, shape, np.float32)
+        for j in range(k_out):
+            what = f"P({op})->{so} {k_in}->{k_out} shape={shape} shard {j}"
+            assert got[j].shape == ref[j].shape, what
+            if op == "max":
+                assert_bits_equal(got[j], ref[j].astype(np.float32), what)
+            else:
+                local_parts = [orc.scatter(p, so, k_out)[j] for p in parts]
+                assert_psum_close(got[j], local_parts, ref[j], what)
+        if so == orc.B:
+            for j in range(1, k_out):
+                assert_bits_equal(got[j], got[0], f"B copies 0 and {j} of P({op})->B across")
+
+
+@pytest.mark.parametrize("k_in,k_out", COUNTS)
+@pytest.mark.parametrize("op", ["sum", "max"])
+@pytest.mark.parametrize("si", [orc.S0, orc.S1, orc.B])
+def test_boxing_into_partial_across(k_in, k_out, op, si):
+    """S(a) -> P, B -> P onto another placement: values placed bit-exactly, identity elsewhere"""
+    so = orc.P_SUM if op == "sum" else orc.P_MAX
+    for n, shape in enumerate(SHAPES):
+        T = rnd_f32(400 + n, shape)
+        ins = orc.scatter(T, si, k_in)
+        ref = orc.boxing_across(ins, si, so, k_out)
+        got = run(ins, si, k_in, so, k_out, shape, np.float32)
+        for j in range(k_out):
+            assert got[j].shape == shape
+            assert np.array_equal(got[j].astype(np.float64), ref[j]), f"{si}->{so} {k_in}->{k_out} shape={shape} shard {j}"
+        assert np.array_equal(orc.assemble([g.astype(np.float64) for g in got], so), T.astype(np.float64))
+
+
+@pytest.mark.parametrize("k_in,k_out", COUNTS)
+@pytest.mark.parametrize("op", ["sum", "max"])
+def test_partial_to_partial_across(k_in, k_out, op):
+    """P -> P: partial i lands on device i mod k_out, several combined in input order in fp32"""
+    s = orc.P_SUM if op == "sum" else orc.P_MAX
+    for n, shape in enumerate(SHAPES):
+        T = rnd_f32(600 + n, shape)
+        parts = random_partials(700 + 20 * n, T, k_in, op)
+        ref = orc.boxing_across(parts, s, s, k_out)
+        got = run(parts, s, k_in, s, k_out, shape, np.float32)
+        for j in range(k_out):
+            mine = parts[j::k_out]
+            what = f"P({op})->P({op}) {k_in}->{k_out} shape={shape} shard {j}"
+            if op == "max" or len(mine) <= 1:
+                assert_bits_equal(got[j], ref[j].astype(np.float32), what)
+            else:
+                assert_psum_close(got[j], mine, ref[j], what)
+                acc = mine[0].copy()                     # the documented order, reproduced exactly
+                for p in mine[1:]:
+                    acc = (acc + p).astype(np.float32)
+                assert_bits_equal(got[j], acc, what + " (fp32 input-order sum)")
+
+
+@pytest.mark.parametrize("k_in,k_out,si,so", [(16, 4, orc.S0, orc.B), (4, 16, orc.S1, orc.B), (16, 8, orc.S0, orc.S1),
+                                              (8, 16, orc.S1, orc.S1), (3, 5, orc.B, orc.B), (5, 3, orc.B, orc.S0)])
+def test_relayout_across_at_scale(k_in, k_out, si, so):
+    """64 MiB of 16-bit words: many chunks of the chunked all-gather walk, uneven device counts"""
+    shape = (4096, 8192)
+    # the pattern repeats every 8 rows at this width: fold the row number in so that rows differ too
+    T = np.ascontiguousarray(wl.pattern_u16(shape)) ^ (np.arange(shape[0], dtype=np.uint16) * np.uint16(40503))[:, None]
+    ins = orc.scatter(T, si, k_in)
+    ref = orc.boxing_across(ins, si, so, k_out)
+    got = run(ins, si, k_in, so, k_out, shape, np.uint16)
+    for j, (g, r) in enumerate(zip(got, ref)):
+        assert_bits_equal(g, r, f"{si}->{so} {k_in}->{k_out} shard {j}")
+
+
+def test_all_reduce_across_at_scale():
+    """8 x 16 MiB fp32 partials onto 4 devices, and 3 partials onto 8"""
+    shape = (1024, 4096)
+    T = rnd_f32(950, shape)
+    for k_in, k_out in ((8, 4), (3, 8)):
+        parts = random_partials(960, T, k_in, "sum")
+        ref = orc.boxing_across(parts, orc.P_SUM, orc.B, k_out)
+        got = run(parts, orc.P_SUM, k_in, orc.B, k_out, shape, np.float32)
+        for j in range(k_out):
+            assert_psum_close(got[j], parts, ref[j], f"P->B {k_in}->{k_out} shard {j}")
+            assert_bits_equal(got[j], got[0], "B copies")

@@ -145,6 +145,21 @@ def test_boxing_cast_validation_errors():
     assert status_of(sbp.sbp_boxing_cast, f32_in, sbp.S(0), over, sbp.B, k, st) == -7          # output over the input
 
 
+def test_boxing_across_validation_errors():
+    st = 0
+    a3, b5 = fake(3, 8, 16), fake(5, 8, 16, base=0x20000000)
+    assert status_of(sbp.sbp_boxing_across, a3, sbp.S(0), 3, b5, sbp.B, 0, st) == -2            # k_out out of range
+    assert status_of(sbp.sbp_boxing_across, a3, sbp.S(0), 65, b5, sbp.B, 5, st) == -2           # k_in out of range
+    assert status_of(sbp.sbp_boxing_across, a3, sbp.P_SUM, 3, b5, sbp.P_MAX, 5, st) == -6       # the reduction cannot change
+    assert status_of(sbp.sbp_boxing_across, a3, sbp.S(0), 3, fake(5, 8, 8, base=0x20000000), sbp.B, 5, st) == -3
+    assert status_of(sbp.sbp_boxing_across, a3, sbp.S(0), 3, fake(5, 8, 16, sbp.BF16, base=0x20000000), sbp.B, 5, st) == -4
+    assert status_of(sbp.sbp_boxing_across, fake(3, 8, 16, sbp.BF16), sbp.P_SUM, 3, fake(5, 8, 16, sbp.BF16, base=0x20000000),
+                     sbp.B, 5, st) == -4                                                        # partial values are fp32
+    assert status_of(sbp.sbp_boxing_across, a3, 7, 3, b5, sbp.B, 5, st) == -5                   # not a signature
+    over = fake(5, 8, 16, base=0x10000000)
+    assert status_of(sbp.sbp_boxing_across, a3, sbp.S(0), 3, over, sbp.B, 5, st) == -7          # output over the input
+
+
 def test_2d_validation_errors():
     k0, k1 = 2, 2
     S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
