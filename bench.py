@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -486,7 +486,51 @@ def bench_zero(args, cfg, sbp, wl, torch, np):
                        k, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
 
 
-OTHER_WORKLOADS = {"dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
+def bench_across(args, cfg, sbp, wl, torch, np):
+    """Boxing between disjoint placements (Sec. 3.2, Table 2 column "disjoint"): a pipeline-stage
+    boundary where the producer runs on 8 logical devices and the consumer on 4 others.  Activations
+    T[16384,16384] 16-bit words: S(0) on 8 -> S(0) on 4, S(0) on 8 -> B on 4; partial results
+    [8192,4096] fp32: P(sum) on 8 -> B on 4, P(sum) on 8 -> S(0) on 4."""
+    ki, ko = 8, 4
+    R, C = 16384, 16384
+    arena = make_arena(torch, np, args.stagger)
+    a8 = arena([(R // ki, C)] * ki, torch.int16)
+    for i in range(ki):
+        a8[i].copy_(torch.from_numpy(wl.pattern_u16((R, C), rows=np.arange(i * (R // ki), (i + 1) * (R // ki))).view(np.int16)))
+    a4 = arena([(R // ko, C)] * ko, torch.int16)
+    b4 = arena([(R, C)] * ko, torch.int16)
+    PR, PC = 8192, 4096
+    p8 = arena([(PR, PC)] * ki, torch.float32)
+    for i in range(ki):
+        p8[i].normal_(0.0, 0.02)
+    pb4 = arena([(PR, PC)] * ko, torch.float32)
+    ps4 = arena([(PR // ko, PC)] * ko, torch.float32)
+    A8, A4, B4 = (sbp.SbpTensor(x, R, C, sbp.BF16) for x in (a8, a4, b4))
+    P8, PB4, PS4 = (sbp.SbpTensor(x, PR, PC, sbp.F32) for x in (p8, pb4, ps4))
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_boxing_across(A8, sbp.S(0), ki, A4, sbp.S(0), ko, st),
+                lambda st: sbp.sbp_boxing_across(A8, sbp.S(0), ki, B4, sbp.B, ko, st),
+                lambda st: sbp.sbp_boxing_across(P8, sbp.P_SUM, ki, PB4, sbp.B, ko, st),
+                lambda st: sbp.sbp_boxing_across(P8, sbp.P_SUM, ki, PS4, sbp.S(0), ko, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    t, pt = 2.0 * R * C, 4.0 * PR * PC
+    by = [2 * t, (1 + ko) * t, (ki + ko) * pt, (ki + 1) * pt]
+    g = [by[i] / ms[i] / 1e6 for i in range(4)]
+    names = ["s0x8_to_s0x4", "s0x8_to_bx4", "psumx8_to_bx4", "psumx8_to_s0x4"]
+    kernels = {}
+    for n, m, r in zip(names, ms, g):
+        kernels[n + "_ms"] = round(m, 4)
+        kernels[n + "_gbps"] = round(r, 1)
+    roof = {"bound": "hbm", "kernel": "sbp_boxing_across P(sum) on 8 -> B on 4 (8 x 128 MiB read, 4 x 128 MiB written)",
+            "achieved": round(g[2], 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g[2] / PEAK_HBM_GBPS, 4), "traffic": None}
+    return result_line(args, "boxing between placements, 8 -> 4 logical devices: T[16384,16384] 16-bit words S(0)->S(0), S(0)->B; "
+                             "[8192,4096] fp32 partials P(sum)->B, P(sum)->S(0)",
+                       ki, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
+
+
+OTHER_WORKLOADS = {"across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
                    "zero": bench_zero}
 
 

@@ -42,6 +42,11 @@ struct BoxParams {
     int32_t axis_out;     // split axis of the output (S outputs), else -1
     int32_t vec_elems;    // elements per vector access
     int32_t sbp_same;     // M_IDENT: signature (decides the local shape)
+    // M_S2S with both sides split along the SAME axis (ki != ko): only ki + ko - 1 of the ki * ko
+    // (input, output) pairs overlap at most; the launcher lists them here so that no workgroup is
+    // started for an empty pair (npairs == 0: task t is pair (t / ko, t % ko))
+    int32_t npairs;
+    uint8_t pair_i[2 * SBP_MAX_K], pair_j[2 * SBP_MAX_K];
 };
 
 struct Task {
@@ -84,7 +89,7 @@ __host__ __device__ inline Task make_task(const BoxParams& p, int32_t t) {
             break;
         }
         case M_S2S: {
-            const int32_t i = t / ko, j = t % ko;   // in_i -> out_j
+            const int32_t i = p.npairs ? p.pair_i[t] : t / ko, j = p.npairs ? p.pair_j[t] : t % ko;   // in_i -> out_j
             int64_t irb, irl, icb, icl, orb, orl, ocb, ocl;
             range_of(p.rows, ki, i, p.axis_in == 0, irb, irl);
             range_of(p.cols, ki, i, p.axis_in == 1, icb, icl);
@@ -596,6 +601,25 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     } else {
         p.mode = M_S2S;   // also S(a) -> S(a) between different device counts
         tasks = ki * ko;
+        if (p.axis_in == p.axis_out) {
+            // same axis: walk the two balanced splits side by side and keep the pairs that overlap
+            const int64_t n = p.axis_in == 0 ? plan.rows : plan.cols;
+            int32_t i = 0, j = 0, np = 0;
+            while (i < ki && j < ko) {
+                const int64_t ib = split_begin(n, ki, i), ie = ib + split_len(n, ki, i);
+                const int64_t jb = split_begin(n, ko, j), je = jb + split_len(n, ko, j);
+                if ((ib > jb ? ib : jb) < (ie < je ? ie : je)) {
+                    p.pair_i[np] = (uint8_t)i;
+                    p.pair_j[np] = (uint8_t)j;
+                    ++np;
+                }
+                if (ie <= je) ++i;
+                if (je <= ie) ++j;
+            }
+            if (np == 0) return SBP_OK;   // an empty axis
+            p.npairs = np;
+            tasks = np;
+        }
     }
     if (tasks > 65535) return SBP_ERR_UNSUPPORTED;
 
@@ -641,7 +665,11 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     // Reductions of at most 32 MiB per source do better with four consecutive vectors per lane (8 x 16 MiB
     // all-reduce: 5.6 against 5.0 TB/s; 8 x 128 MiB: 5.65 against 5.75, so large ones stay at one).
     const int unroll = (reduce && vbytes == 16 && max_units <= ((int64_t)1 << 21)) ? 4 : 1;
-    int64_t cap_total = reduce ? 65536 : 131072;
+    // Workgroups in the whole grid, at most.  A copy workgroup that moves a single 4 KB piece costs more to
+    // start than to run: with 131072 of them a 2 x 512 MiB relayout ran at 3.2-4.7 TB/s, with 32768 (four
+    // pieces each, grid-stride) at 5.4-6.0, and 2 x 1 GiB went from 5.5-5.7 to 5.8-5.9; 8192 is slower
+    // again.  Reductions issue k loads per vector and are indifferent between 32768 and 65536.
+    const int64_t cap_total = reduce ? 65536 : 32768;
     int64_t bx = (max_units + (int64_t)BOX_THREADS * unroll - 1) / ((int64_t)BOX_THREADS * unroll);
     const int64_t cap = (cap_total + tasks - 1) / tasks;
     if (bx > cap) bx = cap;
