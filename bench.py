@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -530,7 +530,69 @@ def bench_across(args, cfg, sbp, wl, torch, np):
                        ki, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
 
 
-OTHER_WORKLOADS = {"across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
+def bench_clock_probe(args, cfg, sbp, wl, torch, np):
+    """Diagnostic, not a workload of the paper: GEMM2 of the MLP block, (S1,S0)->P(sum), run back to back for
+    a few seconds with N(0, 0.02) operands and again with all-zero operands, while `rocm-smi --showclocks`
+    samples the shader clock.  Same kernel, same launches: the difference is what the chip's power
+    management does with the operand data."""
+    import subprocess
+    import threading
+    k, M, N, K = 8, 8192, 4096, 16384
+    arena = make_arena(torch, np, args.stagger)
+    out = {}
+    for mode in ("normal", "zero"):
+        xs = arena([(M, K // k)] * k, torch.bfloat16)
+        ws = arena([(K // k, N)] * k, torch.bfloat16)
+        ys = arena([(M, N)] * k, torch.float32)
+        for t in xs + ws:
+            t.zero_() if mode == "zero" else t.normal_(0.0, 0.02)
+        X, W, Y = sbp.SbpTensor(xs, M, K, sbp.BF16), sbp.SbpTensor(ws, K, N, sbp.BF16), sbp.SbpTensor(ys, M, N, sbp.F32)
+        clocks, stop = [], threading.Event()
+
+        def sampler():
+            while not stop.is_set():
+                try:
+                    txt = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+                    for ln in txt.splitlines():
+                        if "sclk" in ln and "Mhz" in ln:
+                            clocks.append(int(ln.split("(")[1].split("Mhz")[0]))
+                except Exception:
+                    pass
+                stop.wait(0.3)
+
+        for _ in range(5):
+            sbp.sbp_matmul(X, sbp.S(1), W, sbp.S(0), Y, sbp.P_SUM, k)
+        torch.cuda.synchronize()
+        th = threading.Thread(target=sampler)
+        th.start()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0, n = time.perf_counter(), 0
+        e0.record()
+        while time.perf_counter() - t0 < 3.0:
+            for _ in range(50):
+                sbp.sbp_matmul(X, sbp.S(1), W, sbp.S(0), Y, sbp.P_SUM, k)
+            n += 50
+            torch.cuda.synchronize()
+        e1.record()
+        torch.cuda.synchronize()
+        stop.set()
+        th.join()
+        ms = e0.elapsed_time(e1) / n
+        steady = sorted(clocks[1:]) if len(clocks) > 2 else sorted(clocks)
+        out[mode] = (ms, 2.0 * M * N * K / ms / 1e9, steady[len(steady) // 2] if steady else None, n)
+        del xs, ws, ys, X, W, Y
+        torch.cuda.empty_cache()
+    kernels = {"gemm2_normal_ms": round(out["normal"][0], 4), "gemm2_normal_tflops": round(out["normal"][1], 1),
+               "sclk_mhz_normal": out["normal"][2], "gemm2_zero_ms": round(out["zero"][0], 4),
+               "gemm2_zero_tflops": round(out["zero"][1], 1), "sclk_mhz_zero": out["zero"][2],
+               "calls_each": [out["normal"][3], out["zero"][3]]}
+    roof = {"bound": "mfma", "kernel": "sbp_matmul (S1,S0)->P(sum), N(0,0.02) operands, sustained", "achieved": round(out["normal"][1], 1),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(out["normal"][1] / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "diagnostic: sustained GEMM2 of the MLP block with N(0,0.02) and with all-zero operands, shader clock sampled",
+                       k, out["normal"][1], "TFLOP/s", out["normal"][0], kernels, roof)
+
+
+OTHER_WORKLOADS = {"clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
                    "zero": bench_zero}
 
 
