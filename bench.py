@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe", "tiny"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -249,11 +249,11 @@ def time_stages(torch, stages_of, steps, warmup):
     return [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / steps for i in range(n)], wall
 
 
-def result_line(args, workload, k, value, unit, wall_ms, kernels, roofline):
+def result_line(args, workload, k, value, unit, wall_ms, kernels, roofline, dtype="bf16"):
     return {"metric": f"SBP matmul TFLOP/s (% MFMA peak) + boxing GB/s (% HBM peak), k={k}",
             "value": round(value, 3), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "bf16", "data": "synthetic", "config": {"workload": workload, "k": k, "gemm_variant": args.variant},
+            "dtype": dtype, "data": "synthetic", "config": {"workload": workload, "k": k, "gemm_variant": args.variant},
             "kernels": kernels, "roofline": roofline}
 
 
@@ -592,7 +592,39 @@ def bench_clock_probe(args, cfg, sbp, wl, torch, np):
                        k, out["normal"][1], "TFLOP/s", out["normal"][0], kernels, roof)
 
 
-OTHER_WORKLOADS = {"clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
+def bench_tiny(args, cfg, sbp, wl, torch, np):
+    """The small fp32 configuration (k = 2): latency only.  X[64,128] S(1) x W[128,96] S(0) -> 2 fp32 partials
+    [64,96]; boxing P(sum)->B and P(sum)->S(0).  Reported in microseconds per call."""
+    k = cfg["k"]
+    (M, K), N = cfg["X"]["shape"], cfg["W"]["shape"][1]
+    x = [torch.from_numpy(wl.uniform(wl.SEED_BASE, cfg["X"]["id"], (M, K), -1.0, 1.0, None, np.arange(*wl.split_range(K, k, i)))
+                          .astype(np.float32)).cuda().contiguous() for i in range(k)]
+    w = [torch.from_numpy(wl.uniform(wl.SEED_BASE, cfg["W"]["id"], (K, N), -1.0, 1.0, np.arange(*wl.split_range(K, k, i)), None)
+                          .astype(np.float32)).cuda().contiguous() for i in range(k)]
+    y = [torch.empty(M, N, dtype=torch.float32, device="cuda") for _ in range(k)]
+    yb = [torch.empty(M, N, dtype=torch.float32, device="cuda") for _ in range(k)]
+    ys = [torch.empty(wl.split_range(M, k, i)[1] - wl.split_range(M, k, i)[0], N, dtype=torch.float32, device="cuda") for i in range(k)]
+    X, W = sbp.SbpTensor(x, M, K, sbp.F32), sbp.SbpTensor(w, K, N, sbp.F32)
+    Y, YB, YS = (sbp.SbpTensor(t, M, N, sbp.F32) for t in (y, yb, ys))
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_matmul(X, sbp.S(1), W, sbp.S(0), Y, sbp.P_SUM, k, st),
+                lambda st: sbp.sbp_boxing(Y, sbp.P_SUM, YB, sbp.B, k, st),
+                lambda st: sbp.sbp_boxing(Y, sbp.P_SUM, YS, sbp.S(0), k, st)]
+
+    ms, wall = time_stages(torch, stages_of, max(args.steps, 200), max(args.warmup, 20))
+    ref = sum(a.double() @ b.double() for a, b in zip(x, w))
+    err = float((yb[0].double() - ref).abs().max() / ref.abs().max())
+    kernels = {"matmul_us": round(ms[0] * 1e3, 2), "boxing_p2b_us": round(ms[1] * 1e3, 2), "boxing_p2s_us": round(ms[2] * 1e3, 2),
+               "max_rel_err_after_p2b": err, "timed_calls": max(args.steps, 200)}
+    roof = {"bound": "latency", "kernel": "sbp_matmul fp32 64x128x96 on 2 devices", "achieved": round(ms[0] * 1e3, 2), "peak": None,
+            "unit": "us per call", "frac": None, "traffic": None}
+    flops = 2.0 * M * K * N
+    return result_line(args, "small fp32 configuration, k=2: X[64,128] S(1) x W[128,96] S(0) -> P(sum); boxing P->B, P->S(0); latency only",
+                       k, flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof, dtype="f32")
+
+
+OTHER_WORKLOADS = {"tiny": bench_tiny, "clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
                    "zero": bench_zero}
 
 
