@@ -146,3 +146,29 @@ def test_all_reduce_across_at_scale():
         for j in range(k_out):
             assert_psum_close(got[j], parts, ref[j], f"P->B {k_in}->{k_out} shard {j}")
             assert_bits_equal(got[j], got[0], "B copies")
+
+
+@pytest.mark.parametrize("k_in,k_out", [(64, 63), (63, 64), (64, 5), (5, 64), (33, 7)])
+def test_across_many_devices(k_in, k_out):
+    """device counts at the library's limit: the same-axis pair list (up to k_in + k_out - 1 entries), run-time
+    source counts in the reductions, devices that hold no rows at all"""
+    shape = (130, 192)
+    T = rnd_f32(1200, shape)
+    for si, so in ((orc.S0, orc.S0), (orc.S1, orc.S1), (orc.S0, orc.S1), (orc.S1, orc.B), (orc.B, orc.S0)):
+        ins = orc.scatter(T, si, k_in)
+        ref = orc.boxing_across(ins, si, so, k_out)
+        got = run(ins, si, k_in, so, k_out, shape, np.float32)
+        for j, (g, r) in enumerate(zip(got, ref)):
+            assert_bits_equal(g, r, f"{si}->{so} {k_in}->{k_out} shard {j}")
+    parts = random_partials(1300, T, k_in, "sum")
+    for so in (orc.B, orc.S0, orc.P_SUM):
+        ref = orc.boxing_across(parts, orc.P_SUM, so, k_out)
+        got = run(parts, orc.P_SUM, k_in, so, k_out, shape, np.float32)
+        for j in range(k_out):
+            mine = parts[j::k_out] if so == orc.P_SUM else [orc.scatter(p, so, k_out)[j] for p in parts]
+            if not mine:
+                assert not got[j].any()
+            else:
+                assert_psum_close(got[j], mine, ref[j], f"P(sum)->{so} {k_in}->{k_out} shard {j}")
+    got = run(orc.scatter(T, orc.S1, k_in), orc.S1, k_in, orc.P_MAX, k_out, shape, np.float32)
+    assert np.array_equal(orc.assemble([g.astype(np.float64) for g in got], orc.P_MAX), T.astype(np.float64))
