@@ -300,9 +300,10 @@ __device__ inline float mfma_epilogue(float v) {
 //   fp32: one 32 x 32 block at a time, row pitch 128 B.  Row R is kept at R ^ ((R >> 2) & 1): the two
 //         half-waves write rows R and R + 4 in one instruction and so land in different bank halves;
 //         the 16-byte reads of rows 2g, 2g + 1 by one 16-lane group do as well.
-//   bf16: one 32-row x 64-column strip at a time, row pitch 128 B.  Neighbouring lanes first swap one
-//         value (DPP quad permute) so that the even lane holds columns (c, c + 1) of row R and the odd
-//         lane columns (c - 1, c) of row R + 1, packed into one dword; the 64-byte half of the row that
+//   bf16: one 32-row x 64-column strip at a time, row pitch 128 B.  Every lane rounds its two rows of one
+//         column into a dword, neighbouring lanes exchange it (DPP quad permute) and a byte permute leaves
+//         the even lane with columns (c, c + 1) of row R and the odd lane with columns (c - 1, c) of
+//         row R + 1, packed into one dword; the 64-byte half of the row that
 //         block j goes to is j ^ ((R >> 2) & 1), for the same bank reason.
 // Compile-time indices throughout: the accumulators must never be indexed dynamically (they would
 // move to scratch memory).  Edge tiles and result pitches that are not a multiple of 16 bytes take
@@ -400,6 +401,9 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
         } else {
             static_assert(FN % 2 == 0, "bf16 results are staged in strips of two 32-column blocks");
             const int odd = lane & 1;
+            // even lane: row R, columns (c, c + 1) = low halves of (own, neighbour); odd lane: row R + 1, columns
+            // (c - 1, c) = high halves of (neighbour, own).  Byte selectors: 0-3 own, 4-7 neighbour.
+            const uint32_t pick = odd ? 0x03020706u : 0x05040100u;
             [[maybe_unused]] float rm[FM][4];   // EPI_ROWMAX: maxima of rows 32 i + 8 q + lane / 8 over this wave's columns
             if constexpr (EPI == EPI_ROWMAX) {
 #pragma unroll
@@ -417,11 +421,10 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
                     constexpr int j = 2 * jp + decltype(jidx)::value;
                     static_for<8>([&](auto pidx) {
                         constexpr int r = 2 * decltype(pidx)::value;             // rows R (r) and R + 1 (r + 1)
-                        const float v0 = mfma_epilogue<EPI>(acc[i][j][r]);
-                        const float v1 = mfma_epilogue<EPI>(acc[i][j][r + 1]);
-                        const float send = odd ? v0 : v1;
-                        const float recv = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-                        const uint32_t packed = f32_to_bf16x2(odd ? recv : v0, odd ? v1 : recv);
+                        // own column, rows R and R + 1, rounded; then one byte permute with the neighbour's pair
+                        const uint32_t own = f32_to_bf16x2(mfma_epilogue<EPI>(acc[i][j][r]), mfma_epilogue<EPI>(acc[i][j][r + 1]));
+                        const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+                        const uint32_t packed = __builtin_amdgcn_perm(nb, own, pick);
                         constexpr int off = (8 * (r >> 2) + (r & 3)) * 128;
                         *reinterpret_cast<uint32_t*>(stage + (((j & 1) ? w1 : w0) + off)) = packed;
                     });
