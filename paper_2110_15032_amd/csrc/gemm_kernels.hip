@@ -266,7 +266,8 @@ __device__ inline TileCoord map_tile(int bid, int nblk, int tm, int tn, int grou
 // Recipes), which keeps its RELATIVE accuracy in the tail, so gelu of a negative argument does too.
 // P is a degree-5 minimax fit of log2(erfc(z) e^(z^2) / t) on 0 <= z <= 14 made for this kernel (the
 // published fit has degree 9 and 1e-7; this one costs four FMAs less).  Relative error of gelu below
-// 2.2e-5 for every x, a hundredth of a bf16 rounding step.  One rcp, one exp2, eight FMA/mul, no branch.
+// 2.2e-5 for every x whose result is a normal fp32 number, a hundredth of a bf16 rounding step.  One rcp,
+// one exp2, one max, eight FMA/mul, no branch, no select.
 // The argument is clamped to +-14 (erfc underflows before that), so +-inf give +inf and -0.
 __device__ inline float gelu_fast(float x) {
     const float xc = __builtin_amdgcn_fmed3f(x, -14.0f, 14.0f);
@@ -276,11 +277,11 @@ __device__ inline float gelu_fast(float x) {
     p = fmaf(p, t, 0.654060185f);
     p = fmaf(p, t, 0.382378936f);
     p = fmaf(p, t, 1.46516109f);
-    p = fmaf(p, t, -1.82694018f);
+    p = fmaf(p, t, -2.82694018f);                            // constant term less 1: the factor 0.5 below
     const float w = xc * 0.84932180028801905f;               // sqrt(log2(e) / 2): w^2 = z^2 log2 e
-    const float e = t * __builtin_amdgcn_exp2f(fmaf(-w, w, p));   // erfc(|x| / sqrt 2)
-    const float h = 0.5f * xc * e;
-    return x < 0.0f ? h : x - h;                             // x >= 0: 0.5 x (2 - erfc) = x - h
+    const float e = t * __builtin_amdgcn_exp2f(fmaf(-w, w, p));   // 0.5 erfc(|x| / sqrt 2)
+    // 0.5 x (1 + erf) = max(x, 0) - |x| 0.5 erfc(|x| / sqrt 2) for either sign; nothing cancels for x < 0
+    return fmaf(-fabsf(xc), e, fmaxf(x, 0.0f));
 }
 
 template <int EPI>
