@@ -233,3 +233,28 @@ def test_knob_rejects_unknown():
     sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, 0)
     assert status_of(sbp.sbp_set_knob, 99, 0) == -9
     assert status_of(sbp.sbp_set_knob, sbp.KNOB_GEMM_VARIANT, -1) == -9
+
+
+def test_local_shapes_agree_with_the_oracle_on_random_geometry():
+    """property test: the library's split geometry (1-D and on a grid) against the oracle's, which is pinned to
+    numpy's array_split elsewhere"""
+    from hypothesis import given, settings, strategies as st
+
+    sigs = [(sbp.S(0), orc.S0), (sbp.S(1), orc.S1), (sbp.B, orc.B), (sbp.P_SUM, orc.P_SUM), (sbp.P_MAX, orc.P_MAX)]
+
+    @settings(max_examples=300, deadline=None)
+    @given(st.integers(0, 5000), st.integers(0, 5000), st.integers(1, 64), st.integers(0, 4), st.data())
+    def one_d(rows, cols, k, which, data):
+        i = data.draw(st.integers(0, k - 1))
+        abi, o = sigs[which]
+        assert sbp.sbp_local_shape(rows, cols, abi, k, i) == orc.local_shape(rows, cols, o, k, i)
+
+    @settings(max_examples=300, deadline=None)
+    @given(st.integers(0, 3000), st.integers(0, 3000), st.integers(1, 8), st.integers(1, 8), st.integers(0, 4), st.integers(0, 4), st.data())
+    def two_d(rows, cols, k0, k1, w0, w1, data):
+        a, b = data.draw(st.integers(0, k0 - 1)), data.draw(st.integers(0, k1 - 1))
+        abi2, o2 = (sigs[w0][0], sigs[w1][0]), (sigs[w0][1], sigs[w1][1])
+        assert sbp.sbp_local_shape_2d(rows, cols, abi2, k0, k1, a, b) == orc.local_shape2(rows, cols, o2, k0, k1, a, b)
+
+    one_d()
+    two_d()
