@@ -209,6 +209,73 @@ def test_config4_classifier_head_full_size():
     # softmax denominator: s * exp(m) is what does not depend on which of two adjacent bf16 values the max took
     assert np.allclose(np.log(got_s) + got_m, np.log(s) + m, rtol=0, atol=2e-2), "softmax denominator vs oracle"
 
+    # ---- the form bench.py times: row max folded into the logits GEMM; then the sparse cross entropy ----
+    print("config 4: fused row max, cross entropy loss and gradient at full size", flush=True)
+    l2_sh = [torch.full((R, Ci), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    mp2 = vec()
+    L2, MP2 = sbp.SbpTensor(l2_sh, R, C, sbp.BF16), sbp.SbpTensor(mp2, R, 1, sbp.F32)
+    sbp.sbp_matmul_rowmax(Ft, sbp.B, Wt, sbp.S(1), L2, sbp.S(1), MP2, k)
+    sync()
+    for i in range(k):
+        assert torch.equal(l2_sh[i], l_sh[i]), f"logits of the fused call, shard {i}"
+        assert torch.equal(mp2[i], mp[i]), f"fused row max, shard {i}"
+    del l2_sh, L2
+
+    y_host = (wl.uniform(SEED, 40, (R, 1), 0.0, float(C)).astype(np.int64) % C).astype(np.int32)
+    y_host[5, 0] = -1                                   # ignored rows
+    y_host[700, 0] = C
+    g_host = wl.normal(SEED, 41, (R, 1), 1.0, dtype=np.float32)
+    y_dev = torch.from_numpy(y_host).cuda()
+    g_dev = torch.from_numpy(g_host).cuda()
+    lp, lb = vec(), vec()
+    dl_sh = [torch.full((R, Ci), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    Y = sbp.SbpTensor([y_dev] * k, R, 1, sbp.I32)
+    G = sbp.SbpTensor([g_dev] * k, R, 1, sbp.F32)
+    LP, LB = sbp.SbpTensor(lp, R, 1, sbp.F32), sbp.SbpTensor(lb, R, 1, sbp.F32)
+    DL = sbp.SbpTensor(dl_sh, R, C, sbp.BF16)
+    sbp.sbp_xent_loss(L, sbp.S(1), Y, MB, SB, LP, k)
+    sbp.sbp_boxing(LP, sbp.P_SUM, LB, sbp.B, k)
+    sbp.sbp_xent_grad(L, sbp.S(1), Y, MB, SB, G, DL, k)
+    sync()
+
+    # (b) over the whole output on the device: loss = log s + m - L[r, y], gradient = g (exp(L - m) / s - onehot)
+    valid = (y_dev[:, 0] >= 0) & (y_dev[:, 0] < C)
+    picked = torch.zeros(R, dtype=torch.float64, device="cuda")
+    for i in range(k):
+        lo = i * Ci
+        mine = valid & (y_dev[:, 0] >= lo) & (y_dev[:, 0] < lo + Ci)
+        idx = (y_dev[:, 0].long() - lo).clamp(0, Ci - 1)
+        li = l_sh[i].view(torch.bfloat16).gather(1, idx[:, None])[:, 0].double()
+        picked += torch.where(mine, li, torch.zeros_like(li))
+    want_loss = torch.where(valid, torch.log(sb[0][:, 0].double()) + mb[0][:, 0].double() - picked, torch.zeros_like(picked))
+    for j in range(k):
+        assert torch.equal(lb[j], lb[0]), "loss copies"
+    assert torch.allclose(lb[0][:, 0].double(), want_loss, rtol=1e-5, atol=1e-5), "loss over all rows"
+    assert float(lb[0][5, 0]) == 0.0 and float(lb[0][700, 0]) == 0.0
+    for i in range(k):
+        lo = i * Ci
+        pr = torch.exp(l_sh[i].view(torch.bfloat16).double() - mb[0].double()) / sb[0].double()
+        mine = valid & (y_dev[:, 0] >= lo) & (y_dev[:, 0] < lo + Ci)
+        r_idx = torch.nonzero(mine)[:, 0]
+        pr[r_idx, (y_dev[r_idx, 0].long() - lo)] -= 1.0
+        pr *= torch.where(valid, g_dev[:, 0], torch.zeros_like(g_dev[:, 0])).double()[:, None]
+        got = dl_sh[i].view(torch.bfloat16).double()
+        bad = (got - pr).abs() > 2.0 ** -7 * pr.abs() + 1e-30
+        assert not bool(bad.any()), f"gradient shard {i}: {int(bad.sum())} entries more than one bf16 step off"
+        del pr, got, bad
+
+    # (a) the sampled rows through the oracle, from its own logits
+    q_all = np.concatenate(logits_q, axis=1)
+    yr = y_host[rows, 0]
+    ref_loss = orc.softmax_xent_loss(q_all, yr)
+    got_loss = lb[0][ridx, 0].cpu().numpy().astype(np.float64)
+    assert np.allclose(got_loss, ref_loss, rtol=0, atol=2e-2), "loss vs oracle on sampled rows"
+    ref_grad = orc.softmax_xent_grad(q_all, yr, g_host[rows, 0].astype(np.float64))
+    for i in range(k):
+        got = orc.bf16_to_f64(host_u16(dl_sh[i][ridx]))
+        ref = ref_grad[:, i * Ci:(i + 1) * Ci]
+        assert np.all(np.abs(got - ref) <= 2.0 ** -5 * np.abs(ref) + 1e-12), f"gradient vs oracle on sampled rows, shard {i}"
+
 
 # ----------------------------------------------------------------------------------------------
 def test_config5_relayout_full_size():
