@@ -465,7 +465,7 @@ def bench_zero(args, cfg, sbp, wl, torch, np):
     w16 = arena([(R, C)] * k, torch.int16)
     g16 = arena([(R, C)] * k, torch.int16)
     for i in range(k):
-        g16[i].copy_(w16[i].random_(-30000, 30000))     # finite bf16 bit patterns (exponent field below all-ones)
+        g16[i].view(torch.bfloat16).normal_(0.0, 1.0)   # partial gradients, N(0, 1) rounded to bf16
     g32 = arena([(R // k, C)] * k, torch.float32)
     W32, W16 = sbp.SbpTensor(w32, R, C, sbp.F32), sbp.SbpTensor(w16, R, C, sbp.BF16)
     G16, G32 = sbp.SbpTensor(g16, R, C, sbp.BF16), sbp.SbpTensor(g32, R, C, sbp.F32)

@@ -321,3 +321,53 @@ def test_config5_relayout_full_size():
     for j in range(k):
         assert torch.equal(out[j], b[j][j * Rk:(j + 1) * Rk]), f"B->S(0) shard {j}"
         assert int(out[j][0, 0]) == j + 1
+
+
+# ----------------------------------------------------------------------------------------------
+def test_cast_fused_boxing_full_size():
+    """The sharded-optimizer-state workload bench.py times (Sec. 6.4): 2^28 parameters, k = 8.  Forward:
+    fp32 S(0) -> bf16 B; backward: bf16 P(sum) -> fp32 S(0)."""
+    torch = torch_mod()
+    k, R, C = 8, 16384, 16384
+    Rk = R // k
+    w32 = []
+    for i in range(k):
+        rows = np.arange(i * Rk, (i + 1) * Rk)
+        w32.append(torch.from_numpy(wl.normal(SEED, 200, (R, C), 0.02, rows, None, dtype=np.float32)).cuda())
+    w16 = [torch.full((R, C), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    W32, W16 = sbp.SbpTensor(w32, R, C, sbp.F32), sbp.SbpTensor(w16, R, C, sbp.BF16)
+    print("cast + all-gather, 16384 x 16384", flush=True)
+    sbp.sbp_boxing_cast(W32, sbp.S(0), W16, sbp.B, k)
+    sync()
+    # (b) whole output: every copy equals the round-to-nearest-even cast of the assembled tensor (torch's cast as calculator)
+    want = torch.cat(w32, dim=0).to(torch.bfloat16).view(torch.int16)
+    for j in range(k):
+        assert torch.equal(w16[j], want), f"bf16 copy {j}"
+    # (a) sampled rows through the oracle's rounding
+    rows = tile_rows(R, Rk, 3, 21)
+    src = wl.normal(SEED, 200, (R, C), 0.02, rows, None, dtype=np.float32)
+    ridx = torch.from_numpy(rows).cuda()
+    assert_bits_equal(host_u16(w16[3][ridx]), orc.bf16_round(src), "sampled rows vs the oracle's bf16 rounding")
+    del want, w32, W32
+
+    print("cast + reduce-scatter, 8 x 16384 x 16384 bf16 partials", flush=True)
+    g16 = w16                                            # reuse the buffers: k partial gradients, N(0, 1) rounded to bf16
+    gen = torch.Generator(device="cuda").manual_seed(2110150329)
+    for i in range(k):
+        g16[i].view(torch.bfloat16).normal_(0.0, 1.0, generator=gen)
+    g32 = [torch.full((Rk, C), float("nan"), device="cuda") for _ in range(k)]
+    G16, G32 = sbp.SbpTensor(g16, R, C, sbp.BF16), sbp.SbpTensor(g32, R, C, sbp.F32)
+    sbp.sbp_boxing_cast(G16, sbp.P_SUM, G32, sbp.S(0), k)
+    sync()
+    # (b) whole output: fp32 sum in shard order of the exactly widened partials
+    for j in range(k):
+        acc = g16[0][j * Rk:(j + 1) * Rk].view(torch.bfloat16).float()
+        for i in range(1, k):
+            acc = acc + g16[i][j * Rk:(j + 1) * Rk].view(torch.bfloat16).float()
+        assert torch.equal(g32[j], acc), f"fp32 slice {j}"
+    # (a) sampled rows through the oracle (fp64 sum of the widened partials), to the P(sum) bar
+    for j in (0, 5):
+        loc = np.array([0, 17, Rk - 1])
+        parts = [orc.bf16_to_f64(host_u16(g16[i][j * Rk + torch.from_numpy(loc).cuda()])) for i in range(k)]
+        ref = orc.assemble(parts, orc.P_SUM)
+        assert_psum_close(g32[j][torch.from_numpy(loc).cuda()].cpu().numpy(), parts, ref, f"sampled rows of slice {j}")
