@@ -371,3 +371,99 @@ def test_cast_fused_boxing_full_size():
         parts = [orc.bf16_to_f64(host_u16(g16[i][j * Rk + torch.from_numpy(loc).cuda()])) for i in range(k)]
         ref = orc.assemble(parts, orc.P_SUM)
         assert_psum_close(g32[j][torch.from_numpy(loc).cuda()].cpu().numpy(), parts, ref, f"sampled rows of slice {j}")
+
+
+# ----------------------------------------------------------------------------------------------
+def test_uvw_deferred_boxing_full_size():
+    """The Y = U V W workload bench.py times (Sec. 3.3): U[4096,16384] S(1), V[16384,4096] S(0), W[4096,1024] B,
+    bf16, k = 8.  Deferred: (UV) stays 8 fp32 partials, each times W (Table 1 row 4), one P->B on Y.
+    Immediate: P->B on (UV), then row 6.  Sampled rows of both against the oracle's U V W."""
+    torch = torch_mod()
+    k, M, K1, N1, N2 = 8, 4096, 16384, 4096, 1024
+
+    def bits(tid, shape, std, rows=None, cols=None):
+        return wl.to_bf16_bits(wl.normal(SEED, tid, shape, std, rows, cols, dtype=np.float32))
+
+    u_host = [bits(100, (M, K1), 1.0, cols=np.arange(*wl.split_range(K1, k, i))) for i in range(k)]
+    v_host = [bits(101, (K1, N1), 0.02, rows=np.arange(*wl.split_range(K1, k, i))) for i in range(k)]
+    w_host = bits(102, (N1, N2), 0.02)
+    u_sh, v_sh = [dev_u16(x) for x in u_host], [dev_u16(x) for x in v_host]
+    w_sh = [dev_u16(w_host)] * k
+    U, V, W = sbp.SbpTensor(u_sh, M, K1, sbp.BF16), sbp.SbpTensor(v_sh, K1, N1, sbp.BF16), sbp.SbpTensor(w_sh, N1, N2, sbp.BF16)
+    f32 = lambda r, c: [torch.full((r, c), float("nan"), device="cuda") for _ in range(k)]      # noqa: E731
+    uv, uvb, yp, yl, ye = f32(M, N1), f32(M, N1), f32(M, N2), f32(M, N2), f32(M, N2)
+    UV, UVB = sbp.SbpTensor(uv, M, N1, sbp.F32), sbp.SbpTensor(uvb, M, N1, sbp.F32)
+    YP, YL, YE = (sbp.SbpTensor(t, M, N2, sbp.F32) for t in (yp, yl, ye))
+    print("U V W: deferred and immediate boxing at full size", flush=True)
+    sbp.sbp_matmul(U, sbp.S(1), V, sbp.S(0), UV, sbp.P_SUM, k)
+    sbp.sbp_matmul(UV, sbp.P_SUM, W, sbp.B, YP, sbp.P_SUM, k)
+    sbp.sbp_boxing(YP, sbp.P_SUM, YL, sbp.B, k)
+    sbp.sbp_boxing(UV, sbp.P_SUM, UVB, sbp.B, k)
+    sbp.sbp_matmul(UVB, sbp.B, W, sbp.B, YE, sbp.B, k)
+    sync()
+    # (b) whole output: copies identical; the two orders of boxing agree to accumulation-order noise
+    for j in range(1, k):
+        assert torch.equal(yl[j], yl[0]) and torch.equal(ye[j], ye[0]) and torch.equal(uvb[j], uvb[0])
+    scale = float(yl[0].abs().max())
+    assert float((yl[0] - ye[0]).abs().max()) <= 1e-4 * scale, "deferred vs immediate boxing"
+    # (a) sampled rows through the oracle: the partial products one by one, then the whole chain
+    rows = tile_rows(M, 256, 3, 31)
+    ridx = torch.from_numpy(rows).cuda()
+    Wd = orc.bf16_to_f64(w_host)
+    chain = np.zeros((len(rows), N2))
+    for i in range(k):
+        part = orc.matmul(orc.bf16_to_f64(u_host[i][rows]), orc.bf16_to_f64(v_host[i]))          # (UV)_i, fp64
+        assert_matmul_close(uv[i][ridx].cpu().numpy(), part, 2e-2, f"partial {i} of U V")
+        yi = orc.matmul(part, Wd)
+        assert_matmul_close(yp[i][ridx].cpu().numpy(), yi, 2e-2, f"partial {i} of (U V) W")
+        chain += yi
+    assert_matmul_close(yl[0][ridx].cpu().numpy(), chain, 2e-2, "Y, boxing deferred")
+    assert_matmul_close(ye[0][ridx].cpu().numpy(), chain, 2e-2, "Y, boxing immediate")
+
+
+# ----------------------------------------------------------------------------------------------
+def test_boxing_between_placements_full_size():
+    """The placement-boundary workload bench.py times (Table 2, column "disjoint"): 8 -> 4 logical devices.
+    T[16384,16384] 16-bit words S(0) -> S(0) and S(0) -> B; [8192,4096] fp32 partials P(sum) -> B and
+    P(sum) -> S(0)."""
+    torch = torch_mod()
+    ki, ko, R, C = 8, 4, 16384, 16384
+    a8 = [dev_u16(wl.pattern_u16((R, C), rows=np.arange(i * (R // ki), (i + 1) * (R // ki))) ^ np.uint16(257 * i)) for i in range(ki)]
+    whole = torch.cat(a8, dim=0)
+    a4 = [torch.full((R // ko, C), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(ko)]
+    b4 = [torch.full((R, C), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(ko)]
+    A8, A4, B4 = (sbp.SbpTensor(x, R, C, sbp.BF16) for x in (a8, a4, b4))
+    print("between placements: relayout of 512 MiB", flush=True)
+    sbp.sbp_boxing_across(A8, sbp.S(0), ki, A4, sbp.S(0), ko)
+    sbp.sbp_boxing_across(A8, sbp.S(0), ki, B4, sbp.B, ko)
+    sync()
+    for j in range(ko):
+        assert torch.equal(a4[j], whole[j * (R // ko):(j + 1) * (R // ko)]), f"S(0) slice {j}"
+        assert torch.equal(b4[j], whole), f"B copy {j}"
+    # sampled rows against the oracle's own routing of the generator's words
+    rows = np.array([0, 2047, 2048, 9000, R - 1])
+    want = np.stack([wl.pattern_u16((R, C), rows=np.array([r]))[0] ^ np.uint16(257 * (r // (R // ki))) for r in rows])
+    ref = orc.boxing_across([want], orc.S0, orc.B, 1)[0]          # one device holding the sampled rows: identity routing
+    assert_bits_equal(host_u16(b4[2][torch.from_numpy(rows).cuda()]), ref, "sampled rows of a B copy")
+    del a8, a4, b4, whole
+
+    print("between placements: 8 x 128 MiB partials", flush=True)
+    PR, PC = 8192, 4096
+    gen = torch.Generator(device="cuda").manual_seed(2110150330)
+    p8 = [torch.empty(PR, PC, device="cuda").normal_(0.0, 0.02, generator=gen) for _ in range(ki)]
+    pb4 = [torch.full((PR, PC), float("nan"), device="cuda") for _ in range(ko)]
+    ps4 = [torch.full((PR // ko, PC), float("nan"), device="cuda") for _ in range(ko)]
+    P8, PB4, PS4 = (sbp.SbpTensor(x, PR, PC, sbp.F32) for x in (p8, pb4, ps4))
+    sbp.sbp_boxing_across(P8, sbp.P_SUM, ki, PB4, sbp.B, ko)
+    sbp.sbp_boxing_across(P8, sbp.P_SUM, ki, PS4, sbp.S(0), ko)
+    sync()
+    acc = p8[0].clone()
+    for i in range(1, ki):
+        acc += p8[i]                                               # fp32, input order
+    for j in range(ko):
+        assert torch.equal(pb4[j], acc), f"all-reduce copy {j}"
+        assert torch.equal(ps4[j], acc[j * (PR // ko):(j + 1) * (PR // ko)]), f"reduce-scatter slice {j}"
+    loc = torch.from_numpy(np.array([0, 4097, PR - 1])).cuda()
+    parts = [p[loc].cpu().numpy() for p in p8]
+    ref = orc.boxing_across([x.astype(np.float64) for x in parts], orc.P_SUM, orc.B, 1)[0]
+    assert_psum_close(pb4[1][loc].cpu().numpy(), parts, ref, "sampled rows of the all-reduce vs the oracle")
