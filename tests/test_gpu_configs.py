@@ -8,7 +8,13 @@ The oracle cannot recompute whole outputs at these sizes in seconds, so each tes
       shard-order sum of the partials the GPU itself produced, relayouts equal to slices of the
       uploaded global tensor.
 Inputs come from the seeded generator only; nothing the HIP path produced is fed to the oracle.
+
+SBP_FULL_ORACLE=1 in the environment replaces the row samples of the MLP block and of the classifier
+head by ALL rows (the weight gradient is always compared in full): the whole output through the
+oracle, about two minutes of host time.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -20,6 +26,7 @@ from workloads import CONFIGS
 
 pytestmark = pytest.mark.gpu
 SEED = wl.SEED_BASE
+FULL = os.environ.get("SBP_FULL_ORACLE") == "1"
 
 
 def bf16_window(spec, rows=None, cols=None):
@@ -77,7 +84,8 @@ def test_config2_mlp_block_full_size():
     assert not torch.isnan(acc).any()
 
     # (a) sampled token rows through the oracle, every 256-row tile hit
-    rows = tile_rows(T, 256, 3, 7)
+    rows = np.arange(T) if FULL else tile_rows(T, 256, 3, 7)
+    print(f"config 2: {len(rows)} of {T} token rows through the oracle", flush=True)
     Xr = orc.bf16_to_f64(bf16_window(cfg["X"], rows=rows))
     W1h = [orc.bf16_to_f64(host_u16(w)) for w in w1_sh]     # the uploaded words themselves (generator output)
     W2h = [orc.bf16_to_f64(host_u16(w)) for w in w2_sh]
@@ -188,7 +196,8 @@ def test_config4_classifier_head_full_size():
     del lf
 
     # (a) sampled feature rows through the oracle (all 10^6 classes of each), shard by shard
-    rows = tile_rows(R, 256, 3, 11)
+    rows = np.arange(R) if FULL else tile_rows(R, 256, 3, 11)
+    print(f"config 4: {len(rows)} of {R} feature rows through the oracle", flush=True)
     Fr = orc.bf16_to_f64(Fw[rows])
     ridx = torch.from_numpy(rows).cuda()
     m_loc, logits_q = [], []
