@@ -54,7 +54,6 @@ void spans_of(const sbp_tensor_t* t, sbp_t s, int32_t k, std::vector<Span>& v) {
 }
 bool overlap(const Span& a, const Span& b) { return a.lo < b.hi && b.lo < a.hi; }
 
-// outputs must be pairwise disjoint and disjoint from every input
 // Two-dimensional signatures (Sec. 3.3): s[0] places the tensor on the k0 groups, s[1] each group's
 // tensor on its k1 devices; device (a, b) is shard a * k1 + b.
 Local local_of2(int64_t rows, int64_t cols, const sbp_t* s, int32_t k0, int32_t k1, int32_t a, int32_t b) {
@@ -92,6 +91,7 @@ void spans_of2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t k1, st
         }
 }
 
+// outputs must be pairwise disjoint and disjoint from every input
 int32_t check_alias(const std::vector<Span>& outs, const std::vector<Span>& ins) {
     for (size_t a = 0; a < outs.size(); ++a) {
         for (size_t b = a + 1; b < outs.size(); ++b)
@@ -196,7 +196,6 @@ static int32_t matmul_impl(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* 
     spans_of(x, sx, k, ins);
     spans_of(w, sw, k, ins);
     spans_of(y, sy, k, outs);
-    // a B output written k times to one buffer would be k writers of the same bytes: refuse it too
     if (rowmax) {
         if (sy != SBP_S(1)) return SBP_ERR_SIGNATURE;   // only a column-split result has partial row maxima
         if (epilogue != SBP_EPI_NONE) return SBP_ERR_UNSUPPORTED;
@@ -211,6 +210,7 @@ static int32_t matmul_impl(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* 
             outs.push_back({lo, lo + (uintptr_t)y->rows * 4});
         }
     }
+    // (a B output written k times to one buffer would be k writers of the same bytes: refused as well)
     if ((st = check_alias(outs, ins)) != SBP_OK) return st;
 
     GemmPlan plan{};
