@@ -514,7 +514,7 @@ void launch_reduce_k(const BoxParams& p, dim3 grid, hipStream_t st) {
 template <int OP>
 void launch_reduce(const BoxParams& p, dim3 grid, int unroll, hipStream_t st) {
     if (p.vec_elems == 4) {
-        if (unroll == 4) launch_reduce_k<f32x4, OP, 4>(p, grid, st);
+        if (unroll == 8) launch_reduce_k<f32x4, OP, 8>(p, grid, st);
         else launch_reduce_k<f32x4, OP, 1>(p, grid, st);
     } else if (p.vec_elems == 2) launch_reduce_k<f32x2, OP, 1>(p, grid, st);
     else launch_reduce_k<float, OP, 1>(p, grid, st);
@@ -662,9 +662,10 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
             return launch_status(__func__);
         }
     }
-    // Reductions of at most 32 MiB per source do better with four consecutive vectors per lane (8 x 16 MiB
-    // all-reduce: 5.6 against 5.0 TB/s; 8 x 128 MiB: 5.65 against 5.75, so large ones stay at one).
-    const int unroll = (reduce && vbytes == 16 && max_units <= ((int64_t)1 << 21)) ? 4 : 1;
+    // Reductions of at most 32 MiB per source do better with eight consecutive vectors per lane (8 x 16 MiB
+    // all-reduce: 49.5 us against 52.5 us with four and 54.7 us with one; reduce-scatter 29.2 / 30.5 / 31.8 us),
+    // large ones with one (8 x 128 MiB: 365 us, against 378 us with four and 386 us with eight).
+    const int unroll = (reduce && vbytes == 16 && max_units <= ((int64_t)1 << 21)) ? 8 : 1;
     // Workgroups in the whole grid, at most.  A copy workgroup that moves a single 4 KB piece costs more to
     // start than to run: with 131072 of them a 2 x 512 MiB relayout ran at 3.2-4.7 TB/s, with 32768 (four
     // pieces each, grid-stride) at 5.4-6.0, and 2 x 1 GiB went from 5.5-5.7 to 5.8-5.9; 8192 is slower
