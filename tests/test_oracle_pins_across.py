@@ -141,3 +141,37 @@ def test_mixing_reductions_is_refused():
     T = RNG.standard_normal((4, 4))
     with pytest.raises(ValueError):
         orc.boxing_across(_shards(T, P_SUM, 2), P_SUM, P_MAX, 3)
+
+
+def test_reassembly_invariant_on_random_geometry():
+    """property test: any shape, any two device counts, any valid pair of signatures"""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=150, deadline=None)
+    @given(st.integers(0, 23), st.integers(0, 23), st.integers(1, 9), st.integers(1, 9), st.integers(0, 4), st.integers(0, 4),
+           st.integers(0, 2 ** 31 - 1))
+    def check(rows, cols, k_in, k_out, a, b, seed):
+        si, so = ALL[a], ALL[b]
+        if not _valid(si, so):
+            return
+        rng = np.random.default_rng(seed)
+        T = rng.standard_normal((rows, cols))
+        if si == P_SUM:
+            parts = [rng.standard_normal(T.shape) for _ in range(k_in - 1)]
+            ins = parts + [T - np.sum(parts, axis=0) if parts else T.copy()]
+        elif si == P_MAX:
+            who = rng.integers(0, k_in, size=T.shape)
+            ins = [np.where(who == i, T, T - 1.0 - np.abs(rng.standard_normal(T.shape))) for i in range(k_in)]
+        else:
+            ins = orc.scatter(T, si, k_in)
+        out = orc.boxing_across(ins, si, so, k_out)
+        assert len(out) == k_out
+        for j in range(k_out):
+            assert out[j].shape == orc.local_shape(rows, cols, so, k_out, j)
+        np.testing.assert_allclose(orc.assemble(out, so), T, rtol=0, atol=1e-11)
+        if k_in == k_out and so not in (P_SUM, P_MAX):
+            same = orc.boxing(ins, si, so, k_in)
+            for x, y in zip(out, same):
+                np.testing.assert_allclose(x, y, rtol=0, atol=1e-11)
+
+    check()
