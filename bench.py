@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
     ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe", "tiny"],
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe", "tiny", "grid"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -624,7 +624,53 @@ def bench_tiny(args, cfg, sbp, wl, torch, np):
                        k, flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof, dtype="f32")
 
 
-OTHER_WORKLOADS = {"tiny": bench_tiny, "clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
+def bench_grid(args, cfg, sbp, wl, torch, np):
+    """Two-dimensional SBP (Sec. 3.3, Table 3) on a 2 x 4 grid of logical devices, at the MLP block's sizes:
+    row 1: X[8192,4096] (S(0),B) x W[4096,16384] (B,S(1)) -> Y (S(0),S(1)) bf16;
+    row 2: X[8192,16384] (S(0),S(1)) x W[16384,4096] (B,S(0)) -> Y (S(0),P(sum)) fp32, then boxing along the
+    inner axis (S(0),P) -> (S(0),B): an all-reduce inside each group of 4."""
+    k0, k1 = 2, 4
+    k = k0 * k1
+    S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
+    arena = make_arena(torch, np, args.stagger)
+
+    def fill(ts, std):
+        for t in ts:
+            t.view(torch.bfloat16).normal_(0.0, std)
+        return ts
+
+    M, D, F = 8192, 4096, 16384
+    x1 = fill(arena([(M // k0, D)] * k, torch.int16), 1.0)            # (S0, B): rows by group, copies inside
+    w1 = fill(arena([(D, F // k1)] * k, torch.int16), 0.02)           # (B, S1): columns by device inside every group
+    y1 = arena([(M // k0, F // k1)] * k, torch.int16)
+    x2 = fill(arena([(M // k0, F // k1)] * k, torch.int16), 1.0)      # (S0, S1)
+    w2 = fill(arena([(F // k1, D)] * k, torch.int16), 0.02)           # (B, S0): rows by device inside every group
+    y2 = arena([(M // k0, D)] * k, torch.float32)                     # (S0, P)
+    y2b = arena([(M // k0, D)] * k, torch.float32)                    # (S0, B)
+    X1, W1, Y1 = sbp.SbpTensor(x1, M, D, sbp.BF16), sbp.SbpTensor(w1, D, F, sbp.BF16), sbp.SbpTensor(y1, M, F, sbp.BF16)
+    X2, W2 = sbp.SbpTensor(x2, M, F, sbp.BF16), sbp.SbpTensor(w2, F, D, sbp.BF16)
+    Y2, Y2B = sbp.SbpTensor(y2, M, D, sbp.F32), sbp.SbpTensor(y2b, M, D, sbp.F32)
+
+    def stages_of(s):
+        return [lambda st: sbp.sbp_matmul_2d(X1, (S0, B_), W1, (B_, S1), Y1, (S0, S1), k0, k1, st),
+                lambda st: sbp.sbp_matmul_2d(X2, (S0, S1), W2, (B_, S0), Y2, (S0, P), k0, k1, st),
+                lambda st: sbp.sbp_boxing_2d(Y2, (S0, P), Y2B, (S0, B_), k0, k1, st)]
+
+    ms, wall = time_stages(torch, stages_of, args.steps, args.warmup)
+    flops = 2.0 * M * D * F
+    box_bytes = 2.0 * k * (M // k0) * D * 4
+    kernels = {"row1_s0b_x_bs1_ms": round(ms[0], 4), "row1_tflops": round(flops / ms[0] / 1e9, 2),
+               "row2_s0s1_x_bs0_ms": round(ms[1], 4), "row2_tflops": round(flops / ms[1] / 1e9, 2),
+               "boxing_inner_p2b_ms": round(ms[2], 4), "boxing_inner_p2b_gbps": round(box_bytes / ms[2] / 1e6, 1)}
+    tf = flops / ms[1] / 1e9
+    roof = {"bound": "mfma", "kernel": "sbp_matmul_2d (S(0),S(1)) x (B,S(0)) -> (S(0),P(sum))", "achieved": round(tf, 2),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "two-dimensional SBP on a 2 x 4 grid: Table 3 row 1 and row 2 at the MLP block's sizes, "
+                             "all-reduce of the partial results inside every group",
+                       k, 2 * flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
+
+
+OTHER_WORKLOADS = {"grid": bench_grid, "tiny": bench_tiny, "clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
                    "zero": bench_zero}
 
 
