@@ -476,3 +476,63 @@ def test_boxing_between_placements_full_size():
     parts = [p[loc].cpu().numpy() for p in p8]
     ref = orc.boxing_across([x.astype(np.float64) for x in parts], orc.P_SUM, orc.B, 1)[0]
     assert_psum_close(pb4[1][loc].cpu().numpy(), parts, ref, "sampled rows of the all-reduce vs the oracle")
+
+
+# ----------------------------------------------------------------------------------------------
+def test_grid_2x4_full_size():
+    """The two-dimensional workload bench.py times (Sec. 3.3, Table 3) on a 2 x 4 grid at the MLP block's sizes:
+    row 1 (S0,B) x (B,S1) -> (S0,S1), row 2 (S0,S1) x (B,S0) -> (S0,P), then the all-reduce inside each group."""
+    torch = torch_mod()
+    k0, k1, M, D, F = 2, 4, 8192, 4096, 16384
+    k = k0 * k1
+    S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
+    Mg, Fd = M // k0, F // k1
+
+    def bits(tid, shape, std, rows=None, cols=None):
+        return wl.to_bf16_bits(wl.normal(SEED, tid, shape, std, rows, cols, dtype=np.float32))
+
+    # row 1: X1[M,D] rows by group, W1[D,F] columns by device
+    x1_h = [bits(300, (M, D), 1.0, rows=np.arange(a * Mg, (a + 1) * Mg)) for a in range(k0)]
+    w1_h = [bits(301, (D, F), 0.02, cols=np.arange(b * Fd, (b + 1) * Fd)) for b in range(k1)]
+    x1_d, w1_d = [dev_u16(x) for x in x1_h], [dev_u16(w) for w in w1_h]
+    x1 = [x1_d[a] for a in range(k0) for b in range(k1)]
+    w1 = [w1_d[b] for a in range(k0) for b in range(k1)]
+    y1 = [torch.full((Mg, Fd), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    # row 2: X2[M,F] rows by group and columns by device, W2[F,D] rows by device
+    x2_h = [[bits(302, (M, F), 1.0, rows=np.arange(a * Mg, (a + 1) * Mg), cols=np.arange(b * Fd, (b + 1) * Fd)) for b in range(k1)]
+            for a in range(k0)]
+    w2_h = [bits(303, (F, D), 0.02, rows=np.arange(b * Fd, (b + 1) * Fd)) for b in range(k1)]
+    w2_d = [dev_u16(w) for w in w2_h]
+    x2 = [dev_u16(x2_h[a][b]) for a in range(k0) for b in range(k1)]
+    w2 = [w2_d[b] for a in range(k0) for b in range(k1)]
+    y2 = [torch.full((Mg, D), float("nan"), device="cuda") for _ in range(k)]
+    y2b = [torch.full((Mg, D), float("nan"), device="cuda") for _ in range(k)]
+    X1, W1, Y1 = sbp.SbpTensor(x1, M, D, sbp.BF16), sbp.SbpTensor(w1, D, F, sbp.BF16), sbp.SbpTensor(y1, M, F, sbp.BF16)
+    X2, W2 = sbp.SbpTensor(x2, M, F, sbp.BF16), sbp.SbpTensor(w2, F, D, sbp.BF16)
+    Y2, Y2B = sbp.SbpTensor(y2, M, D, sbp.F32), sbp.SbpTensor(y2b, M, D, sbp.F32)
+    print("grid 2 x 4: Table 3 rows 1 and 2 at full size, inner all-reduce", flush=True)
+    sbp.sbp_matmul_2d(X1, (S0, B_), W1, (B_, S1), Y1, (S0, S1), k0, k1)
+    sbp.sbp_matmul_2d(X2, (S0, S1), W2, (B_, S0), Y2, (S0, P), k0, k1)
+    sbp.sbp_boxing_2d(Y2, (S0, P), Y2B, (S0, B_), k0, k1)
+    sync()
+    # (b) whole output: inside each group the copies are identical and equal the fp32 sum of its partials in device order
+    for a in range(k0):
+        acc = y2[a * k1].clone()
+        for b in range(1, k1):
+            acc += y2[a * k1 + b]
+        for b in range(k1):
+            assert torch.equal(y2b[a * k1 + b], acc), f"group {a} copy {b}"
+    # (a) sampled rows of every device's local product through the oracle
+    rows = tile_rows(Mg, 256, 3, 41)
+    ridx = torch.from_numpy(rows).cuda()
+    for a in range(k0):
+        Xr = orc.bf16_to_f64(x1_h[a][rows])
+        total = np.zeros((len(rows), D))
+        for b in range(k1):
+            ref1 = orc.matmul(Xr, orc.bf16_to_f64(w1_h[b]))
+            got1 = orc.bf16_to_f64(host_u16(y1[a * k1 + b][ridx]))
+            assert_matmul_close(got1, orc.bf16_to_f64(orc.bf16_round(ref1)), 2e-2, f"row 1, device ({a},{b})")
+            ref2 = orc.matmul(orc.bf16_to_f64(x2_h[a][b][rows]), orc.bf16_to_f64(w2_h[b]))
+            assert_matmul_close(y2[a * k1 + b][ridx].cpu().numpy(), ref2, 2e-2, f"row 2 partial, device ({a},{b})")
+            total += ref2
+        assert_matmul_close(y2b[a * k1][ridx].cpu().numpy(), total, 2e-2, f"row 2 after the inner all-reduce, group {a}")
