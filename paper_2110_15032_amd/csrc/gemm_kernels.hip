@@ -106,8 +106,10 @@ __device__ inline int kswz(int row) {
 // LDS image of a not-KC tile: [BKT][R] with the 16-byte chunks of kk-row q permuted by XOR with
 // nswz(q).  A ds_read_b64_tr_b16 serves 32 lanes per pass: 4 consecutive kk-rows x 64 contiguous
 // bytes.  Row pitch is a multiple of 256 B, so without the permutation the 4 rows share banks;
-// moving row q by (q % 4) * 64 B spreads them over all 64 banks.
-__device__ inline int nswz(int krow) { return (krow & 3) << 2; }
+// moving row q by (q % 4) * 64 B spreads them over all 64 banks.  The 16x16x32 fragments read kk-rows
+// q and q + 8 in one pass, 32 bytes each: rows with bit 3 set move by another 32 B (a constant inside
+// every pass of the 32x32x16 fragments, so those are not affected).
+__device__ inline int nswz(int krow) { return ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1); }
 
 template <int R, bool KC, int NT, int BKT = BK>
 struct Tile {
@@ -203,6 +205,40 @@ struct Tile {
             // consecutive elements (row s / 4, element group s % 4) of a 4 x 16 block and receives
             // column s of it.  Two reads (kk-rows +0..3 and +4..7, same swizzle) give the 8 values.
             const int off0 = lo[blk] + ks * 16 * (R * 2);
+            const int off1 = off0 + 4 * (R * 2);
+            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off0));
+            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off1));
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            const s16x8 v = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    // ---- operands of v_mfma_f32_16x16x32_bf16 (BKT = 32: one instruction spans the whole stage) ----
+    // Lane l holds the 8 values kk = 8 (l / 16) + 0..7 of row (block base + l % 16).
+    // One lane offset serves every block.  KC: a 16-row block adds 16 * ROWB (kswz repeats every 16 rows).
+    // Not KC: block b adds 2 b to the chunk index; the wave's base chunk is a multiple of 16 and b < 8, so
+    // that sum is an OR, and the swizzle being an XOR, block b's offset is block 0's with (b << 5) flipped.
+    __device__ static int lane_offset16(int wave_base, int lane) {
+        static_assert(BKT == 32, "one 16x16x32 instruction per 32-deep stage");
+        int off;
+        if constexpr (KC) {
+            const int row = wave_base + (lane & 15);
+            off = row * ROWB + (((lane >> 4) ^ kswz<BKT>(row)) << 4);
+        } else {              // the second read adds 4 kk-rows
+            const int s = lane & 15, g = lane >> 4;
+            const int krow = 8 * g + (s >> 2);
+            const int chunk = (wave_base >> 3) + ((s & 3) >> 1);
+            off = krow * (R * 2) + ((chunk ^ nswz(krow)) << 4) + (s & 1) * 8;
+        }
+        asm("" : "+v"(off));
+        return off;
+    }
+    __device__ static bf16x8 frag16(const char* lds_tile, int lo, int blk) {
+        if constexpr (KC) {
+            return *reinterpret_cast<const bf16x8*>(lds_tile + (lo + blk * 16 * ROWB));
+        } else {
+            const int off0 = lo ^ (blk << 5);
             const int off1 = off0 + 4 * (R * 2);
             const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off0));
             const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off1));
@@ -502,6 +538,170 @@ __device__ __attribute__((always_inline)) inline void store_tile(const f32x16 (&
         });
     });
     if constexpr (LOADS_FIRST) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));   // edge tile: loads and stores alike
+}
+
+// Epilogue for accumulators of v_mfma_f32_16x16x32_bf16 (persistent kernel): every 16 x 16 block holds
+// D[4 (lane / 16) + r][lane % 16] = acc[r], r = 0..3.  Same per-wave 4 KB window, same read side (each lane
+// ends up with 16 consecutive bytes of a row; eight 128-byte row segments per store instruction) and the
+// same global addressing as store_tile; only the way the accumulators enter the window differs.
+//   fp32: a 32 x 32 region (2 x 2 blocks) at a time, row pitch 128 B.  One write instruction covers rows
+//         4 g + r for g = lane / 16 = 0..3, 16 dwords each: row R is kept at R ^ ((R >> 2) & 1) and its
+//         two 64-byte halves are swapped when (R >> 3) & 1, which puts the four rows on 4 x 16 banks.
+//   bf16: a 32-row x 64-column strip (2 x 4 blocks) at a time.  Lanes round and pair their rows R, R + 1
+//         and exchange with the neighbouring column as in store_tile; one write instruction covers rows
+//         4 g + (lane & 1), 8 dwords each: the 32-byte column group j is kept at j ^ g.
+template <int BM, int BN, int TM, int TN, int EPI, typename OutT>
+__device__ __attribute__((always_inline)) inline void store_tile16(const f32x4 (&acc)[TM / 16][TN / 16], const GemmShard& s, int m0, int n0, int wm, int wn, int lane, char* stage) {
+    constexpr int FM = TM / 32, FN = TN / 32;       // 32 x 32 regions, as in store_tile
+    OutT* C = static_cast<OutT*>(s.c);
+    constexpr int EPV = 16 / (int)sizeof(OutT);
+    const bool whole = m0 + BM <= s.m && n0 + BN <= s.n && s.ldc % EPV == 0;
+    [[maybe_unused]] const bool stream = (s.ldc * (int)sizeof(OutT)) % 128 == 0;
+    // Every lane constant of the epilogue is derived from this copy of the lane id, which the compiler cannot
+    // move out of the tile loop: they are recomputed per tile (a few dozen instructions) instead of occupying
+    // registers all through the reduction loop, which has none to spare.
+    asm volatile("" : "+v"(lane));
+    const int g = lane >> 4, c = lane & 15;
+    if (whole) {
+        const int wave = (int)(threadIdx.x >> 6);
+        const int h = lane >> 5;
+        OutT* cg = C + (int64_t)(m0 + wm * TM + (lane >> 3)) * s.ldc + (n0 + wn * TN + (lane & 7) * EPV);
+        if constexpr (sizeof(OutT) == 4) {
+            // read side: logical row (lane / 8) + 8 q, logical 16-byte chunk lane % 8
+            int rd0 = wave * STAGE_BYTES + (((lane >> 3) ^ h) * 128) + (lane & 7) * 16;            // q even
+            int rd1 = wave * STAGE_BYTES + (((lane >> 3) ^ h) * 128) + (((lane & 7) ^ 4) * 16);      // q odd: halves swapped
+            asm volatile("" : "+v"(rd0));
+            asm volatile("" : "+v"(rd1));
+            // write side: [r parity][jb]
+            int w[2][2];
+#pragma unroll
+            for (int rp = 0; rp < 2; ++rp)
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb) {
+                    w[rp][jb] = wave * STAGE_BYTES + (4 * g + (rp ^ (g & 1))) * 128 + (16 * (jb ^ (g >> 1)) + c) * 4;
+                    asm volatile("" : "+v"(w[rp][jb]));
+                }
+            static_for<FM * FN>([&](auto idx) {
+                constexpr int i = decltype(idx)::value / FN, j = decltype(idx)::value % FN;
+                static_for<2>([&](auto ibx) {
+                    constexpr int ib = decltype(ibx)::value;
+                    static_for<2>([&](auto jbx) {
+                        constexpr int jb = decltype(jbx)::value;
+                        static_for<4>([&](auto ridx) {
+                            constexpr int r = decltype(ridx)::value;
+                            constexpr int off = (16 * ib + (r & 2)) * 128;
+                            *reinterpret_cast<float*>(stage + (w[r & 1][jb] + off)) = mfma_epilogue<EPI>(acc[2 * i + ib][2 * j + jb][r]);
+                        });
+                    });
+                });
+                __builtin_amdgcn_wave_barrier();
+                static_for<4>([&](auto qidx) {
+                    constexpr int q = decltype(qidx)::value;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(stage + (((q & 1) ? rd1 : rd0) + q * 1024));
+                    f32x4* dst = reinterpret_cast<f32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc + j * 32);
+                    if constexpr (decltype(idx)::value == 0 && q == 0) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+                    store16_untracked(dst, v, stream);
+                });
+                __builtin_amdgcn_wave_barrier();
+            });
+        } else {
+            static_assert(TN == 64, "bf16 results are staged in strips of 64 columns");
+            const int odd = lane & 1;
+            const uint32_t pick = odd ? 0x03020706u : 0x05040100u;
+            [[maybe_unused]] float rm[FM][4];
+            if constexpr (EPI == EPI_ROWMAX) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) rm[i][q] = -__builtin_inff();
+            }
+            // read side: logical row (lane / 8) + 8 q, chunk lane % 8; the row's column groups are kept at j ^ g(row)
+            int rd0 = wave * STAGE_BYTES + (lane >> 3) * 128 + (((lane & 7) ^ (2 * h)) * 16);           // q even: g(row) = h
+            int rd1 = wave * STAGE_BYTES + (lane >> 3) * 128 + (((lane & 7) ^ (2 * h + 4)) * 16);       // q odd:  g(row) = h + 2
+            asm volatile("" : "+v"(rd0));
+            asm volatile("" : "+v"(rd1));
+            int w[4];   // [j]
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                w[j] = wave * STAGE_BYTES + (4 * g + odd) * 128 + ((((j ^ g) << 3) + (c >> 1)) * 4);
+                asm volatile("" : "+v"(w[j]));
+            }
+            static_for<FM>([&](auto idx) {
+                constexpr int i = decltype(idx)::value;
+                static_for<2>([&](auto ibx) {
+                    constexpr int ib = decltype(ibx)::value;
+                    static_for<4>([&](auto jidx) {
+                        constexpr int j = decltype(jidx)::value;
+                        static_for<2>([&](auto pidx) {
+                            constexpr int r = 2 * decltype(pidx)::value;
+                            const uint32_t own = f32_to_bf16x2(mfma_epilogue<EPI>(acc[2 * i + ib][j][r]), mfma_epilogue<EPI>(acc[2 * i + ib][j][r + 1]));
+                            const uint32_t nb = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)own, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+                            const uint32_t packed = __builtin_amdgcn_perm(nb, own, pick);
+                            constexpr int off = (16 * ib + r) * 128;
+                            *reinterpret_cast<uint32_t*>(stage + (w[j] + off)) = packed;
+                        });
+                    });
+                });
+                __builtin_amdgcn_wave_barrier();
+                static_for<4>([&](auto qidx) {
+                    constexpr int q = decltype(qidx)::value;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + (((q & 1) ? rd1 : rd0) + q * 1024));
+                    u32x4* dst = reinterpret_cast<u32x4*>(cg + (int64_t)(i * 32 + q * 8) * s.ldc);
+                    if constexpr (EPI == EPI_ROWMAX) {
+                        float mx = fmaxf(__uint_as_float(v[0] << 16), __uint_as_float(v[0] & 0xFFFF0000u));
+#pragma unroll
+                        for (int d = 1; d < 4; ++d) mx = fmaxf(mx, fmaxf(__uint_as_float(v[d] << 16), __uint_as_float(v[d] & 0xFFFF0000u)));
+                        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xF, 0xF, false)));
+                        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xF, 0xF, false)));
+                        mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xF, 0xF, false)));
+                        rm[i][q] = fmaxf(rm[i][q], mx);
+                    }
+                    if constexpr (decltype(idx)::value == 0 && q == 0) __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+                    store16_untracked(dst, v, stream);
+                });
+                __builtin_amdgcn_wave_barrier();
+            });
+            if constexpr (EPI == EPI_ROWMAX) {
+                constexpr int WN_ = BN / TN;
+                float* win = reinterpret_cast<float*>(stage + wave * STAGE_BYTES);
+                if ((lane & 7) == 0) {
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) win[i * 32 + q * 8 + (lane >> 3)] = rm[i][q];
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (wn == 0) {
+#pragma unroll
+                    for (int t = 0; t < TM / 64; ++t) {
+                        const int row = lane + 64 * t;
+                        float mx = win[row];
+#pragma unroll
+                        for (int ww = 1; ww < WN_; ++ww) mx = fmaxf(mx, reinterpret_cast<const float*>(stage + (wave + ww) * STAGE_BYTES)[row]);
+                        atomic_max_f32_untracked(s.rowmax + (m0 + wm * TM + row), mx);
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // edge tiles: element by element, guarded
+    static_for<(TM / 16) * (TN / 16)>([&](auto idx) {
+        constexpr int i = decltype(idx)::value / (TN / 16), j = decltype(idx)::value % (TN / 16);
+        const int n = n0 + wn * TN + j * 16 + c;
+        const int mb = m0 + wm * TM + i * 16 + 4 * g;
+        OutT* cp = C + (int64_t)mb * s.ldc + n;
+        static_for<4>([&](auto ridx) {
+            constexpr int r = decltype(ridx)::value;
+            const int m = mb + r;
+            const float v = mfma_epilogue<EPI>(acc[i][j][r]);
+            if (m < s.m && n < s.n) {
+                store_out_untracked(cp, (int64_t)r * s.ldc, v);
+                if constexpr (EPI == EPI_ROWMAX) atomic_max_f32_untracked(s.rowmax + m, bf16_to_f32(f32_to_bf16(v)));
+            }
+        });
+    });
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(0));   // edge tile: loads and stores alike
 }
 
 // Scheduling hint for one phase of NMFMA matrix instructions: let one LDS read and (for the first NVM
@@ -974,6 +1174,197 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist_kernel(GemmPla
 }
 
 // ------------------------------------------------------------------------------------------------
+// The persistent kernel on v_mfma_f32_16x16x32_bf16.  Same tiles, stages, load stream, counters and
+// barriers as gemm_mfma_persist_kernel; the matrix instruction spans the whole 32-deep stage, its
+// accumulator block is 16 x 16 (four registers), and a step is split by row blocks instead of by
+// reduction halves.  Under a sustained load of random operands the part's power management lets this
+// instruction run at a higher clock than the 32x32x16 form (MFMA-only loop: 2070 against 1843 TFLOP/s).
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int NST, int EPI, typename OutT>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist16_kernel(GemmPlan p, int tm, int tn, int order, int nblk) {
+    constexpr int BKT = 32;
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int FM = TM / 16, FN = TN / 16;       // 16 x 16 blocks per wave
+    static_assert(FM % 2 == 0, "the row blocks are multiplied in two halves");
+    constexpr int HM = FM / 2;
+    constexpr int NDS_A = A_KC ? HM : 2 * HM;                           // LDS reads of half the A fragments
+    constexpr int NDS_B = B_KC ? FN : 2 * FN;                           // ... of all B fragments
+    using TA = Tile<BM, A_KC, NT, BKT>;
+    using TB = Tile<BN, B_KC, NT, BKT>;
+    constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
+    constexpr int WAIT_KEEP = (NST - 2) * NVM;
+    static_assert(NST == 4, "written for four stages");
+    __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA2[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA3[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB2[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB3[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sOut[WM * WN * STAGE_BYTES];   // epilogue windows, one per wave
+    auto stA = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sA0; else if constexpr (I == 1) return sA1; else if constexpr (I == 2) return sA2; else return sA3;
+    };
+    auto stB = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sB0; else if constexpr (I == 1) return sB1; else if constexpr (I == 2) return sB2; else return sB3;
+    };
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int G = gridDim.x;
+
+    // first valid tile at or after virtual block v (uneven shards have fewer tiles than tm x tn)
+    auto next_valid = [&](int v) {
+        for (; v < nblk; v += G) {
+            const TileCoord tc = map_tile(v, nblk, tm, tn, p.groups, order);
+            if (tc.valid && tc.tile_m * BM < p.s[tc.g].m && tc.tile_n * BN < p.s[tc.g].n) break;
+        }
+        return v;
+    };
+
+    // ---- load cursor: always exactly NST - 1 stages ahead of the compute cursor ------------------
+    gbl_char* A = nullptr;
+    gbl_char* B = nullptr;
+    uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+    uint32_t stepa = 0, stepb = 0;
+    const int first = next_valid(blockIdx.x);
+    if (first >= nblk) return;         // nothing for this workgroup
+    auto open_tile = [&](int v) {
+        const TileCoord tc = map_tile(v, nblk, tm, tn, p.groups, order);
+        const GemmShard& s = p.s[tc.g];
+        A = (gbl_char*)s.a;
+        B = (gbl_char*)s.b;
+        // the chunk positions are recomputed from the thread id at every tile: kept across the reduction loop
+        // they would take registers that the loop does not have
+        int t = tid;
+        asm volatile("" : "+v"(t));
+#pragma unroll
+        for (int it = 0; it < TA::PER_THREAD; ++it) offa[it] = TA::src_offset(s.lda, tc.tile_m * BM, s.m, it * NT + t);
+#pragma unroll
+        for (int it = 0; it < TB::PER_THREAD; ++it) offb[it] = TB::src_offset(s.ldb, tc.tile_n * BN, s.n, it * NT + t);
+        stepa = TA::step_bytes(s.lda);
+        stepb = TB::step_bytes(s.ldb);
+    };
+    open_tile(first);
+    // Branch-free: always NVM loads (the wait counts rely on it), then one stage forward.  Because a
+    // tile has a multiple of NST stages, the cursor leaves a tile exactly after step 0 of the tile's
+    // last round; the tile loop below re-opens it there.  Past the last tile the steps are zeroed, so
+    // the last stage is simply re-read (in bounds, never used).
+    auto issue = [&](char* da, char* db) {
+        TA::load_direct_untracked(da, A, offa, wave);
+        TB::load_direct_untracked(db, B, offb, wave);
+        A += stepa;
+        B += stepb;
+    };
+
+    // ---- compute side --------------------------------------------------------------------------
+    // One v_mfma_f32_16x16x32_bf16 spans a whole 32-deep stage.  A step multiplies the upper half of the
+    // row blocks, then the lower half: fa[0] / fa[1] hold the A fragments of the two halves, fb[slot] the
+    // B fragments of a stage (slot = stage parity; both halves use them, so the next stage's go to the
+    // other slot).
+    f32x4 acc[FM][FN];
+    bf16x8 fa[2][HM], fb[2][FN];
+    static_assert((A_KC || (TM % 128 == 0 && FM <= 8)) && (B_KC || (TN % 64 == 0 && FN <= 4)), "see Tile::lane_offset16");
+    const int loa = TA::lane_offset16(wm * TM, lane), lob = TB::lane_offset16(wn * TN, lane);
+    auto read_a = [&](const char* sa, int half) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i) fa[half][i] = TA::frag16(sa, loa, half * HM + i);
+    };
+    auto read_b = [&](const char* sb, int slot) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag16(sb, lob, j);
+    };
+    auto mfmas = [&](int half, int slot) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[half * HM + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[half][i], fb[slot][j], acc[half * HM + i][j], 0, 0, 0);
+    };
+    constexpr int WAIT_STRICT = (WAIT_KEEP & 15) | ((WAIT_KEEP >> 4) << 14) | 0x0070;   // vmcnt(WAIT_KEEP) lgkmcnt(0)
+    // Stores of a tile's epilogue sit in the in-order memory queue in front of the next tile's fourth
+    // stage.  The first two steps of a tile need stages 1 and 2 only, which the epilogue has already
+    // waited for (see store_tile), so they run on a barrier alone (NOWAIT) and the stores drain
+    // underneath them; the third step is the first to wait on the queue again, and its "all but the
+    // two youngest stages" then covers the stores as well.
+    constexpr int WAIT_LDS_ONLY = 0xC07F;   // lgkmcnt(0), vmcnt untouched
+    auto step = [&](auto cur, auto nowait) {
+        constexpr int CUR = decltype(cur)::value;
+        constexpr bool NOWAIT = decltype(nowait)::value;
+        using Nxt = std::integral_constant<int, (CUR + 1) % NST>;
+        using Dst = std::integral_constant<int, (CUR + NST - 1) % NST>;
+        issue(stA(Dst{}), stB(Dst{}));
+        read_a(stA(cur), 1);
+        mfmas(0, CUR & 1);
+        pace<HM * FN, NDS_A, NVM>();
+        __builtin_amdgcn_s_waitcnt(NOWAIT ? WAIT_LDS_ONLY : WAIT_STRICT);
+        __builtin_amdgcn_s_barrier();
+        read_a(stA(Nxt{}), 0);
+        read_b(stB(Nxt{}), (CUR + 1) & 1);
+        mfmas(1, CUR & 1);
+        pace<HM * FN, NDS_A + NDS_B, 0>();
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    using Wait = std::false_type;
+    using NoWait = std::true_type;
+    static_assert(NST == 4, "the tile loop below is written for four stages");
+
+    static_for<NST - 1>([&](auto i) { issue(stA(i), stB(i)); });
+    __builtin_amdgcn_s_waitcnt(0x0070);   // all three stages landed: the first tile starts like every other
+    __builtin_amdgcn_s_barrier();
+    read_a(sA0, 0);
+    read_b(sB0, 0);
+
+    for (int cv = first; cv < nblk;) {
+        const TileCoord tc = map_tile(cv, nblk, tm, tn, p.groups, order);
+        const GemmShard s = p.s[tc.g];
+        const int m0 = tc.tile_m * BM, n0 = tc.tile_n * BN;
+        const int rounds = s.kk / (BKT * NST);
+        const int nv = next_valid(cv + G);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+        // the load cursor has issued this tile's last stage: move it to the next tile
+        auto switch_tile = [&]() {
+            if (nv < nblk) {
+                open_tile(nv);
+            } else {
+                A -= stepa;     // no next tile: keep re-reading the last stage
+                B -= stepb;
+                stepa = 0;
+                stepb = 0;
+            }
+        };
+        step(I0{}, NoWait{});
+        if (rounds == 1) switch_tile();
+        step(I1{}, NoWait{});
+        step(I2{}, Wait{});
+        step(I3{}, Wait{});
+        for (int r = 1; r < rounds; ++r) {
+            step(I0{}, Wait{});
+            if (r == rounds - 1) switch_tile();
+            step(I1{}, Wait{});
+            step(I2{}, Wait{});
+            step(I3{}, Wait{});
+        }
+        store_tile16<BM, BN, TM, TN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
+        cv = nv;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);   // trailing (unused) loads must land before LDS is released
+}
+
+// ------------------------------------------------------------------------------------------------
 // Rows 4 and 5 of Table 1 next to bf16 tensors: one operand is an un-reduced P(sum) partial (fp32),
 // the other a bf16 B tensor, the result again fp32 partials.  Rounding the partial to bf16 would change
 // the sum it stands for, so it is split exactly into three bf16 terms on its way into LDS,
@@ -1167,8 +1558,12 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
         int grid = cus / 8 * 8;
         if (grid > nblk) grid = (int)nblk;
-        hipLaunchKernelGGL((gemm_mfma_persist_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 100, EPI, OutT>), dim3((uint32_t)grid),
-                           dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
+        if constexpr (ODD >= 200)
+            hipLaunchKernelGGL((gemm_mfma_persist16_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 200, EPI, OutT>), dim3((uint32_t)grid),
+                               dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
+        else
+            hipLaunchKernelGGL((gemm_mfma_persist_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 100, EPI, OutT>), dim3((uint32_t)grid),
+                               dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
         return launch_status(__func__);
     }
     void (*kern)(GemmPlan, int, int, int);
@@ -1292,23 +1687,25 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         if (plan.s[g].m && plan.s[g].n && plan.s[g].kk % 128) k128 = false;
     if (plan.epilogue == EPI_ROWMAX) {
         // fused row maximum: persistent bf16 kernel only; anything else is done in two passes by the caller
-        if (!(k128 && max_m > 128 && max_n > 128 && plan.out_dtype == SBP_BF16 && (variant == 0 || variant == 12))) return SBP_ERR_UNSUPPORTED;
+        if (!(k128 && max_m > 128 && max_n > 128 && plan.out_dtype == SBP_BF16 && (variant == 0 || variant == 12 || variant == 16))) return SBP_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(fill_rowmax_kernel, dim3((uint32_t)((max_m + 255) / 256), (uint32_t)plan.groups), dim3(256), 0, stream, plan);
         const int32_t st = launch_status(__func__);
         if (st != SBP_OK) return st;
-        return launch_mfma_layout<256, 256, 2, 4, 104, EPI_ROWMAX, uint16_t>(plan, max_m, max_n, stream);
+        if (variant == 12) return launch_mfma_layout<256, 256, 2, 4, 104, EPI_ROWMAX, uint16_t>(plan, max_m, max_n, stream);
+        return launch_mfma_layout<256, 256, 2, 4, 204, EPI_ROWMAX, uint16_t>(plan, max_m, max_n, stream);
     }
     if (variant == 0) {
         // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages, as one persistent
         // workgroup per compute unit when the reduction length allows it; shapes that would leave most
         // of such a tile empty take the 128 x 128 tile.
-        variant = (max_m > 128 && max_n > 128) ? (k128 ? 12 : 6) : 4;
+        variant = (max_m > 128 && max_n > 128) ? (k128 ? 16 : 6) : 4;
     }
     switch (variant) {
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
         case 4: return launch_mfma_out<128, 128, 2, 2, 0>(plan, max_m, max_n, stream);
         case 6: return launch_mfma_out<256, 256, 2, 4, 4>(plan, max_m, max_n, stream);
         case 12: return k128 ? launch_mfma_out<256, 256, 2, 4, 104>(plan, max_m, max_n, stream) : SBP_ERR_UNSUPPORTED;
+        case 16: return k128 ? launch_mfma_out<256, 256, 2, 4, 204>(plan, max_m, max_n, stream) : SBP_ERR_UNSUPPORTED;
         default: return SBP_ERR_UNSUPPORTED;
     }
 }
