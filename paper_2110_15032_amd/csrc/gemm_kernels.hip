@@ -8,7 +8,9 @@
 //                             registers, two LDS stages of 64 reduction elements.
 //   gemm_mfma_pipe_kernel     the same with 3-5 stages of 32 and partial waits on the load counter.
 //   gemm_mfma_persist_kernel  four stages, one workgroup per compute unit walking many tiles, the next
-//                             tile's loads in flight across the epilogue: the default for large shapes.
+//                             tile's loads in flight across the epilogue.
+//   gemm_mfma_persist16_kernel  the same on v_mfma_f32_16x16x32_bf16 (store_tile16): the default for
+//                             large shapes; under real operands the chip clocks this instruction higher.
 //   gemm_split_kernel         one fp32 operand (a P(sum) partial) split exactly into three bf16 terms.
 // All MFMA kernels share Tile (LDS images, swizzles, fragment reads) and store_tile (epilogue).
 //
@@ -1697,8 +1699,10 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
     if (variant == 0) {
         // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages, as one persistent
         // workgroup per compute unit when the reduction length allows it; shapes that would leave most
-        // of such a tile empty take the 128 x 128 tile.
-        variant = (max_m > 128 && max_n > 128) ? (k128 ? 16 : 6) : 4;
+        // of such a tile empty take the 128 x 128 tile.  The persistent kernel runs on the 16x16x32
+        // matrix instruction, except when neither operand is contiguous along the reduction (there the
+        // fragment addressing leaves it short of registers and the 32x32x16 form is 2 % faster).
+        variant = (max_m > 128 && max_n > 128) ? (k128 ? ((plan.a_kc || plan.b_kc) ? 16 : 12) : 6) : 4;
     }
     switch (variant) {
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);

@@ -231,13 +231,15 @@ def test_matmul_bf16_mfma_shapes(sx, sw, tx, tw, variant):
             assert_matmul_close(g, ref[i], 1e-4, f"bf16->f32 partial, shard {i}")
 
 
-@pytest.mark.parametrize("tx,tw", [(0, 0), (1, 1)])
+@pytest.mark.parametrize("variant", [12, 16])
+@pytest.mark.parametrize("tx,tw", [(0, 0), (1, 1), (1, 0), (0, 1)])
 @pytest.mark.parametrize("sx,sw", [(orc.S0, orc.B), (orc.B, orc.S1), (orc.S1, orc.S0)])
 @pytest.mark.parametrize("kshard", [128, 384])
-def test_matmul_bf16_persistent_kernel(sx, sw, tx, tw, kshard):
-    """variant 12 keeps one workgroup per compute unit and walks it over several output tiles, the
-    next tile's operand loads overlapping the current tile's stores.  270 tiles (more than one per
-    workgroup), interior and ragged edge tiles in every order, one and three rounds of four stages."""
+def test_matmul_bf16_persistent_kernel(sx, sw, tx, tw, kshard, variant):
+    """variants 12 and 16 (the 32x32x16 and the 16x16x32 matrix instruction) keep one workgroup per compute
+    unit and walk it over several output tiles, the next tile's operand loads overlapping the current
+    tile's stores.  270 tiles (more than one per workgroup), interior and ragged edge tiles, every
+    operand layout, one and three rounds of four stages."""
     k = 3
     M, N = 2520, 2104                          # pitches must be multiples of 8 elements
     if sx == orc.S0:
@@ -248,10 +250,12 @@ def test_matmul_bf16_persistent_kernel(sx, sw, tx, tw, kshard):
     X, W = rnd_bf16(3, (M, K)), rnd_bf16(4, (K, N), 0.05)
     Xs, Ws = orc.scatter(X, sx, k), orc.scatter(W, sw, k)
     ref, sy = orc.matmul_sbp([values(x) for x in Xs], sx, [values(w) for w in Ws], sw)
-    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx, tw, variant=12)
+    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx, tw, variant=variant)
     for i in range(k):
         g = got[i] if sy == orc.P_SUM else values(got[i])
-        assert_matmul_close(g, ref[i], 2e-2, f"persistent ({sx},{sw}) trans=({tx},{tw}) shard {i}")
+        assert_matmul_close(g, ref[i], 2e-2, f"persistent v{variant} ({sx},{sw}) trans=({tx},{tw}) shard {i}")
+        if sy == orc.P_SUM:
+            assert_matmul_close(g, ref[i], 1e-4, f"persistent v{variant}: fp32 partial of exact products, shard {i}")
 
 
 @pytest.mark.parametrize("tx,tw", [(0, 0), (1, 0), (0, 1), (1, 1)])
@@ -292,10 +296,11 @@ def test_matmul_bf16_persistent_kernel_uneven_shards():
         X, W = rnd_bf16(5, (M, K)), rnd_bf16(6, (K, N), 0.05)
         Xs, Ws = orc.scatter(X, orc.S0, k), orc.scatter(W, orc.B, k)
         ref, sy = orc.matmul_sbp([values(x) for x in Xs], orc.S0, [values(w) for w in Ws], orc.B)
-        got, _ = run_matmul(Xs, orc.S0, Ws, orc.B, M, K, N, k, variant=12)
-        for i in range(k):
-            assert got[i].shape == ref[i].shape
-            assert_matmul_close(values(got[i]), ref[i], 2e-2, f"uneven S(0) shards, k={k}, shard {i}")
+        for variant in (12, 16):
+            got, _ = run_matmul(Xs, orc.S0, Ws, orc.B, M, K, N, k, variant=variant)
+            for i in range(k):
+                assert got[i].shape == ref[i].shape
+                assert_matmul_close(values(got[i]), ref[i], 2e-2, f"uneven S(0) shards, v{variant}, k={k}, shard {i}")
 
 
 def test_matmul_bf16_odd_shapes_fall_back():
