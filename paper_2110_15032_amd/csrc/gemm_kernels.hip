@@ -240,7 +240,10 @@ struct Tile {
         if constexpr (KC) {
             return *reinterpret_cast<const bf16x8*>(lds_tile + (lo + blk * 16 * ROWB));
         } else {
-            const int off0 = lo ^ (blk << 5);
+            // (as volatile assembly: a plain XOR is loop-invariant, and the compiler would keep one copy per block
+            // in registers all through the reduction loop, which has none to spare)
+            int off0 = lo;
+            if (blk) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(off0) : "v"(lo), "v"(blk << 5));
             const int off1 = off0 + 4 * (R * 2);
             const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off0));
             const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(lds_tile + off1));
@@ -1700,9 +1703,8 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         // Default: the 256 x 256 tile over 8 waves with four 32-deep LDS stages, as one persistent
         // workgroup per compute unit when the reduction length allows it; shapes that would leave most
         // of such a tile empty take the 128 x 128 tile.  The persistent kernel runs on the 16x16x32
-        // matrix instruction, except when neither operand is contiguous along the reduction (there the
-        // fragment addressing leaves it short of registers and the 32x32x16 form is 2 % faster).
-        variant = (max_m > 128 && max_n > 128) ? (k128 ? ((plan.a_kc || plan.b_kc) ? 16 : 12) : 6) : 4;
+        // matrix instruction.
+        variant = (max_m > 128 && max_n > 128) ? (k128 ? 16 : 6) : 4;
     }
     switch (variant) {
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
