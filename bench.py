@@ -35,7 +35,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak, TFLOP/s
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak, GB/s
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
 # calibration copy; summary in profiles/bench_mlp_k8_counters.md).  Offline figures, not re-measured here.
-TRAFFIC_BYTES = {"gemm1": 1.853e9, "gemm2": 3.393e9, "boxing_p2b": 2.174e9}
+TRAFFIC_BYTES = {"gemm1": 1.858e9, "gemm2": 3.390e9, "boxing_p2b": 2.171e9}
 
 
 def parse():
