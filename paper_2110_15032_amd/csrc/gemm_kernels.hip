@@ -1378,7 +1378,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist16_kernel(GemmP
 // bf16 MFMAs, one per term, into the same fp32 accumulator.  Products of bf16 values are exact in
 // fp32, so the result differs from an fp32 GEMM by accumulation order only.  (Inf in the partial gives
 // NaN: inf - inf in the split.)
-// 128 x 128 tile, 4 waves of 64 x 64, two LDS stages of 32 reduction elements: three term tiles of the
+// 128 x 128 tile, 4 waves of 64 x 64 (16 blocks of v_mfma_f32_16x16x32_bf16), two LDS stages of 32 reduction elements: three term tiles of the
 // fp32 operand (written from registers, same chunk order and swizzle as the direct-to-LDS image) and
 // one tile of the bf16 operand (direct to LDS).  F32_B: the fp32 operand is B (row 5), else A (row 4).
 // ------------------------------------------------------------------------------------------------
@@ -1407,7 +1407,7 @@ __device__ inline SplitTerms split_f32x8(const f32x4 a, const f32x4 b) {
 template <bool A_KC, bool B_KC, bool F32_B>
 __global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int tn, int order) {
     constexpr int BM = 128, BN = 128, WN = 2, NT = 256, BKT = 32;
-    constexpr int TM = 64, TN = 64, FM = 2, FN = 2;
+    constexpr int TM = 64, TN = 64, FM = 4, FN = 4;   // 16 x 16 blocks of v_mfma_f32_16x16x32_bf16 (one per 32-deep stage)
     using TA = Tile<BM, A_KC, NT, BKT>;
     using TB = Tile<BN, B_KC, NT, BKT>;
     using TF = std::conditional_t<F32_B, TB, TA>;   // tile type of the fp32 operand
@@ -1442,18 +1442,14 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int
     const uint64_t stepf = (uint64_t)2 * TF::step_bytes(ldf);
     const uint32_t steph = TH::step_bytes(ldh);
 
-    f32x16 acc[FM][FN];
+    f32x4 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    int loa[TA::template nlo<FM>()], lob[TB::template nlo<FN>()];
-#pragma unroll
-    for (int x = 0; x < TA::template nlo<FM>(); ++x) loa[x] = TA::lane_offset(x, wm * TM, lane);
-#pragma unroll
-    for (int x = 0; x < TB::template nlo<FN>(); ++x) lob[x] = TB::lane_offset(x, wn * TN, lane);
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+    const int loa = TA::lane_offset16(wm * TM, lane), lob = TB::lane_offset16(wn * TN, lane);
 
     f32x4 raw[TF::PER_THREAD][2];
     auto fetch = [&]() {   // global -> registers (fp32 operand), global -> LDS (bf16 operand)
@@ -1475,33 +1471,30 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int
         }
     };
     auto compute = [&](const char (*sf)[TF::BYTES], const char* sh) {
+        if constexpr (F32_B) {
+            bf16x8 fa[FM];
 #pragma unroll
-        for (int ks = 0; ks < BKT / 16; ++ks) {
-            if constexpr (F32_B) {
-                bf16x8 fa[FM];
+            for (int i = 0; i < FM; ++i) fa[i] = TA::frag16(sh, loa, i);
 #pragma unroll
-                for (int i = 0; i < FM; ++i) fa[i] = TA::frag(sh, loa, i, ks);
+            for (int term = 0; term < 3; ++term)
 #pragma unroll
-                for (int term = 0; term < 3; ++term)
+                for (int j = 0; j < FN; ++j) {
+                    const bf16x8 fb = TB::frag16(sf[term], lob, j);
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) {
-                        const bf16x8 fb = TB::frag(sf[term], lob, j, ks);
+                    for (int i = 0; i < FM; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb, acc[i][j], 0, 0, 0);
+                }
+        } else {
+            bf16x8 fb[FN];
 #pragma unroll
-                        for (int i = 0; i < FM; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb, acc[i][j], 0, 0, 0);
-                    }
-            } else {
-                bf16x8 fb[FN];
+            for (int j = 0; j < FN; ++j) fb[j] = TB::frag16(sh, lob, j);
 #pragma unroll
-                for (int j = 0; j < FN; ++j) fb[j] = TB::frag(sh, lob, j, ks);
+            for (int term = 0; term < 3; ++term)
 #pragma unroll
-                for (int term = 0; term < 3; ++term)
+                for (int i = 0; i < FM; ++i) {
+                    const bf16x8 fa = TA::frag16(sf[term], loa, i);
 #pragma unroll
-                    for (int i = 0; i < FM; ++i) {
-                        const bf16x8 fa = TA::frag(sf[term], loa, i, ks);
-#pragma unroll
-                        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
-                    }
-            }
+                    for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
+                }
         }
     };
 
@@ -1533,7 +1526,7 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int
         step(I1{}, t + 2 < steps);
     }
     if (steps & 1) step(I0{}, false);
-    store_tile<BM, BN, TM, TN, FM, FN, SBP_EPI_NONE, float>(acc, s, m0, n0, wm, wn, lane, sOut);
+    store_tile16<BM, BN, TM, TN, SBP_EPI_NONE, float>(acc, s, m0, n0, wm, wn, lane, sOut);
 }
 
 template <bool F32_B>
