@@ -238,7 +238,8 @@ int32_t sbp_xent_grad(const sbp_tensor_t* logits, sbp_t sbp_l, const sbp_tensor_
 enum {
     SBP_KNOB_GEMM_VARIANT = 0,  /* 0 = default choice by shape; >0 forces a kernel: 1 generic, 3 = 256x256
                                    tile with two 64-deep stages, 4 = 128x128 tile, 6 = 256x256 with four
-                                   32-deep stages, 12 = 6 as one persistent workgroup per compute unit
+                                   32-deep stages, 7 = 6 on the 16x16x32 matrix instruction,
+                                   12 = 6 as one persistent workgroup per compute unit
                                    (needs every local reduction length to be a multiple of 128), 16 =
                                    12 on the 16x16x32 matrix instruction; a forced kernel that cannot
                                    take the shapes gives SBP_ERR_UNSUPPORTED                           */

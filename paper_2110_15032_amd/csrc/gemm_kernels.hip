@@ -7,6 +7,8 @@
 //                             BM x BN macro-tile per workgroup, global->LDS loads that bypass
 //                             registers, two LDS stages of 64 reduction elements.
 //   gemm_mfma_pipe_kernel     the same with 3-5 stages of 32 and partial waits on the load counter.
+//   gemm_mfma_pipe16_kernel   four stages of 32 on v_mfma_f32_16x16x32_bf16: large shapes whose reduction
+//                             length is a multiple of 64 but not of 128.
 //   gemm_mfma_persist_kernel  four stages, one workgroup per compute unit walking many tiles, the next
 //                             tile's loads in flight across the epilogue.
 //   gemm_mfma_persist16_kernel  the same on v_mfma_f32_16x16x32_bf16 (store_tile16): the default for
@@ -988,6 +990,140 @@ __global__ __launch_bounds__(WM * WN * 64, (BM * BN <= 256 * 128 && WM * WN == 4
     store_tile<BM, BN, TM, TN, FM, FN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
 }
 
+// The pipelined kernel on v_mfma_f32_16x16x32_bf16 (four stages; fragments, step and epilogue as in
+// gemm_mfma_persist16_kernel): shapes whose reduction length is a multiple of 32 but not of 128.
+template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int NST, int EPI, typename OutT>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_pipe16_kernel(GemmPlan p, int tm, int tn, int order) {
+    constexpr int BKT = 32;
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int FM = TM / 16, FN = TN / 16;       // 16 x 16 blocks per wave
+    static_assert(FM % 2 == 0, "the row blocks are multiplied in two halves");
+    constexpr int HM = FM / 2;
+    constexpr int NDS_A = A_KC ? HM : 2 * HM;
+    constexpr int NDS_B = B_KC ? FN : 2 * FN;
+    using TA = Tile<BM, A_KC, NT, BKT>;
+    using TB = Tile<BN, B_KC, NT, BKT>;
+    constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
+    static_assert(NST == 4, "the B fragments alternate between two slots by stage parity");
+    static_assert((NST - 2) * NVM < 64, "vmcnt field");
+    __shared__ __attribute__((aligned(1024))) char sA0[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA1[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA2[TA::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA3[NST > 3 ? TA::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sA4[NST > 4 ? TA::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sB0[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB1[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB2[TB::BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB3[NST > 3 ? TB::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sB4[NST > 4 ? TB::BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) char sOut[WM * WN * STAGE_BYTES];   // epilogue windows, one per wave
+    auto stA = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sA0; else if constexpr (I == 1) return sA1; else if constexpr (I == 2) return sA2;
+        else if constexpr (I == 3) return sA3; else return sA4;
+    };
+    auto stB = [&](auto i) -> char* {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0) return sB0; else if constexpr (I == 1) return sB1; else if constexpr (I == 2) return sB2;
+        else if constexpr (I == 3) return sB3; else return sB4;
+    };
+
+    const TileCoord tc = map_tile(blockIdx.x, gridDim.x, tm, tn, p.groups, order);
+    if (!tc.valid) return;
+    const GemmShard s = p.s[tc.g];
+    const int m0 = tc.tile_m * BM, n0 = tc.tile_n * BN;
+    if (m0 >= s.m || n0 >= s.n) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    gbl_char* A = (gbl_char*)s.a;
+    gbl_char* B = (gbl_char*)s.b;
+
+    uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+#pragma unroll
+    for (int it = 0; it < TA::PER_THREAD; ++it) offa[it] = TA::src_offset(s.lda, m0, s.m, it * NT + tid);
+#pragma unroll
+    for (int it = 0; it < TB::PER_THREAD; ++it) offb[it] = TB::src_offset(s.ldb, n0, s.n, it * NT + tid);
+    const uint32_t stepa = TA::step_bytes(s.lda), stepb = TB::step_bytes(s.ldb);
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 fa[2][HM], fb[2][FN];
+    static_assert((A_KC || (TM % 64 == 0 && FM <= 8)) && (B_KC || (TN % 64 == 0 && FN <= 4)), "see Tile::lane_offset16");
+    const int loa = TA::lane_offset16(wm * TM, lane), lob = TB::lane_offset16(wn * TN, lane);
+    auto read_a = [&](const char* sa, int half) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i) fa[half][i] = TA::frag16(sa, loa, half * HM + i);
+    };
+    auto read_b = [&](const char* sb, int slot) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[slot][j] = TB::frag16(sb, lob, j);
+    };
+    auto mfmas = [&](int half, int slot) {
+#pragma unroll
+        for (int i = 0; i < HM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[half * HM + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[half][i], fb[slot][j], acc[half * HM + i][j], 0, 0, 0);
+    };
+
+    const int steps = s.kk / BKT;
+    int loaded = 0;   // tiles whose loads have been issued; the source pointers sit on tile min(loaded, steps - 1)
+    auto issue = [&](char* da, char* db) {
+        TA::load_direct(da, A, offa, wave);
+        TB::load_direct(db, B, offb, wave);
+        ++loaded;
+        const bool adv = loaded < steps;   // past the last tile the pointer stays: reloads are in bounds, unread
+        A += adv ? stepa : 0u;
+        B += adv ? stepb : 0u;
+    };
+    // s_waitcnt immediate: vmcnt(n), n < 64, split over bits 3:0 and 15:14; expcnt left at "no wait"
+    constexpr int WAIT_KEEP = (NST - 2) * NVM;
+    constexpr int WAIT_IMM = (WAIT_KEEP & 15) | ((WAIT_KEEP >> 4) << 14) | 0x0070;   // ... and lgkmcnt(0)
+
+    auto step = [&](auto cur) {
+        constexpr int CUR = decltype(cur)::value;
+        using Nxt = std::integral_constant<int, (CUR + 1) % NST>;
+        using Dst = std::integral_constant<int, (CUR + NST - 1) % NST>;
+        issue(stA(Dst{}), stB(Dst{}));
+        read_a(stA(cur), 1);
+        mfmas(0, CUR & 1);
+        pace<HM * FN, NDS_A, NVM>();
+        // This wave's part of the next tile has landed (later tiles may still fly) and its own
+        // fragment reads have returned; then a bare hardware barrier.  __syncthreads() is not used:
+        // its workgroup fence counts direct-to-LDS loads as LDS stores and would drain ALL of them.
+        __builtin_amdgcn_s_waitcnt(WAIT_IMM);
+        __builtin_amdgcn_s_barrier();
+        read_a(stA(Nxt{}), 0);
+        read_b(stB(Nxt{}), (CUR + 1) & 1);
+        mfmas(1, CUR & 1);
+        pace<HM * FN, NDS_A + NDS_B, 0>();
+    };
+
+    static_for<NST - 1>([&](auto i) { issue(stA(i), stB(i)); });
+    __builtin_amdgcn_s_waitcnt(WAIT_IMM);
+    __builtin_amdgcn_s_barrier();
+    read_a(sA0, 0);
+    read_b(sB0, 0);
+    int t = 0;
+    for (; t + NST <= steps; t += NST) static_for<NST>([&](auto i) { step(i); });
+    const int rem = steps - t;   // 0 .. NST - 1 steps left, stage numbering continues from 0
+    static_for<NST - 1>([&](auto i) {
+        if (decltype(i)::value < rem) step(i);
+    });
+    __builtin_amdgcn_s_waitcnt(0x0070);   // drain the (unread) trailing loads before LDS is released
+
+    store_tile16<BM, BN, TM, TN, EPI, OutT>(acc, s, m0, n0, wm, wn, lane, sOut);
+}
+
 // ------------------------------------------------------------------------------------------------
 // Persistent form of the pipelined kernel: one workgroup per CU walks its tiles v = b, b + G, ...
 // (G = grid size, a multiple of 8, so a workgroup stays on the XCD the tile walk assigns) and the
@@ -1566,6 +1702,7 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
     }
     void (*kern)(GemmPlan, int, int, int);
     if constexpr (ODD >= 100) kern = nullptr;
+    else if constexpr (ODD >= 50) kern = gemm_mfma_pipe16_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 50, EPI, OutT>;   // 16x16x32 instruction
     else if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
     else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
     hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn));
@@ -1697,12 +1834,13 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
         // workgroup per compute unit when the reduction length allows it; shapes that would leave most
         // of such a tile empty take the 128 x 128 tile.  The persistent kernel runs on the 16x16x32
         // matrix instruction.
-        variant = (max_m > 128 && max_n > 128) ? (k128 ? 16 : 6) : 4;
+        variant = (max_m > 128 && max_n > 128) ? (k128 ? 16 : 7) : 4;
     }
     switch (variant) {
         case 3: return launch_mfma_out<256, 256, 2, 4, 0>(plan, max_m, max_n, stream);
         case 4: return launch_mfma_out<128, 128, 2, 2, 0>(plan, max_m, max_n, stream);
         case 6: return launch_mfma_out<256, 256, 2, 4, 4>(plan, max_m, max_n, stream);
+        case 7: return launch_mfma_out<256, 256, 2, 4, 54>(plan, max_m, max_n, stream);
         case 12: return k128 ? launch_mfma_out<256, 256, 2, 4, 104>(plan, max_m, max_n, stream) : SBP_ERR_UNSUPPORTED;
         case 16: return k128 ? launch_mfma_out<256, 256, 2, 4, 204>(plan, max_m, max_n, stream) : SBP_ERR_UNSUPPORTED;
         default: return SBP_ERR_UNSUPPORTED;

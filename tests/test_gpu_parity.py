@@ -212,7 +212,7 @@ def test_matmul_fp32_every_table1_row(k, sx, sw):
 
 @pytest.mark.parametrize("tx,tw", [(0, 0), (1, 0), (0, 1), (1, 1)])
 @pytest.mark.parametrize("sx,sw", [(orc.S0, orc.B), (orc.B, orc.S1), (orc.S1, orc.S0), (orc.B, orc.B)])
-@pytest.mark.parametrize("variant", [0, 1, 3, 4, 6])
+@pytest.mark.parametrize("variant", [0, 1, 3, 4, 6, 7])
 def test_matmul_bf16_mfma_shapes(sx, sw, tx, tw, variant):
     """several 256-tiles plus ragged M / N tails; K a multiple of 64 per shard.  variant 1 is the
     generic kernel on the same data, the others are MFMA kernel variants (256 x 256 tile with 2 x 64
