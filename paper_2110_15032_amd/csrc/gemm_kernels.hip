@@ -107,6 +107,12 @@ __device__ inline int kswz(int row) {
     if constexpr (BKT == 64) return (row ^ (row >> 3)) & 7;
     else return (row >> 2) & 3;
 }
+// KC tiles read by the 16x16x32 fragments (lane l: row l % 16, chunk l / 16).  The passes of that
+// ds_read_b128 are taken not to be 16 consecutive lanes but lanes {0-3, 12-15, 20-23, 24-27}, then
+// {4-7, 8-11, 16-19, 28-31}, then the same plus 32: a pass mixes rows 0-3 and 12-15 of one chunk column
+// with rows 4-11 of its neighbour.  With q = row / 4, XOR values (0, 3, 2, 1)[q] keep the four rows of
+// equal row % 4 in such a pass on four different chunks (and do so for 16 consecutive lanes as well).
+__device__ inline int kswz16(int row) { return (0 - (row >> 2)) & 3; }
 // LDS image of a not-KC tile: [BKT][R] with the 16-byte chunks of kk-row q permuted by XOR with
 // nswz(q).  A ds_read_b64_tr_b16 serves 32 lanes per pass: 4 consecutive kk-rows x 64 contiguous
 // bytes.  Row pitch is a multiple of 256 B, so without the permutation the 4 rows share banks;
@@ -115,7 +121,8 @@ __device__ inline int kswz(int row) {
 // every pass of the 32x32x16 fragments, so those are not affected).
 __device__ inline int nswz(int krow) { return ((krow & 3) << 2) ^ (((krow >> 3) & 1) << 1); }
 
-template <int R, bool KC, int NT, int BKT = BK>
+// F16: the tile feeds v_mfma_f32_16x16x32_bf16 (frag16) and its KC image is permuted by kswz16.
+template <int R, bool KC, int NT, int BKT = BK, bool F16 = false>
 struct Tile {
     static constexpr int BYTES = R * BKT * 2;
     static constexpr int CHUNKS = BYTES / 16;
@@ -123,6 +130,7 @@ struct Tile {
     static constexpr int CPR = R / 8;        // 16-byte chunks per kk-row of a not-KC tile
     static constexpr int CPK = BKT / 8;      // 16-byte chunks per row of a KC tile
     static constexpr int ROWB = BKT * 2;     // bytes per row of a KC tile
+    __device__ static int ksw(int row) { return F16 ? kswz16(row) : kswz<BKT>(row); }
     static_assert(CHUNKS % NT == 0, "tile must divide over the workgroup");
     static_assert(KC || CPR >= 16, "not-KC swizzle needs at least 16 chunks per row");
 
@@ -134,7 +142,7 @@ struct Tile {
             const int row = p / CPK;
             int g = first + row;
             g = g < limit ? g : limit - 1;
-            return ((uint32_t)g * (uint32_t)ld + (uint32_t)(((p % CPK) ^ kswz<BKT>(row)) * 8)) * 2u;
+            return ((uint32_t)g * (uint32_t)ld + (uint32_t)(((p % CPK) ^ ksw(row)) * 8)) * 2u;
         } else {
             const int krow = p / CPR;
             int col = first + (((p % CPR) ^ nswz(krow)) * 8);
@@ -220,15 +228,16 @@ struct Tile {
 
     // ---- operands of v_mfma_f32_16x16x32_bf16 (BKT = 32: one instruction spans the whole stage) ----
     // Lane l holds the 8 values kk = 8 (l / 16) + 0..7 of row (block base + l % 16).
-    // One lane offset serves every block.  KC: a 16-row block adds 16 * ROWB (kswz repeats every 16 rows).
+    // One lane offset serves every block.  KC: a 16-row block adds 16 * ROWB (kswz16 repeats every 16 rows).
     // Not KC: block b adds 2 b to the chunk index; the wave's base chunk is a multiple of 16 and b < 8, so
     // that sum is an OR, and the swizzle being an XOR, block b's offset is block 0's with (b << 5) flipped.
     __device__ static int lane_offset16(int wave_base, int lane) {
         static_assert(BKT == 32, "one 16x16x32 instruction per 32-deep stage");
         int off;
+        static_assert(F16, "frag16 reads tiles laid out for it");
         if constexpr (KC) {
             const int row = wave_base + (lane & 15);
-            off = row * ROWB + (((lane >> 4) ^ kswz<BKT>(row)) << 4);
+            off = row * ROWB + (((lane >> 4) ^ kswz16(row)) << 4);
         } else {              // the second read adds 4 kk-rows
             const int s = lane & 15, g = lane >> 4;
             const int krow = 8 * g + (s >> 2);
@@ -1002,8 +1011,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_pipe16_kernel(GemmPlan
     constexpr int HM = FM / 2;
     constexpr int NDS_A = A_KC ? HM : 2 * HM;
     constexpr int NDS_B = B_KC ? FN : 2 * FN;
-    using TA = Tile<BM, A_KC, NT, BKT>;
-    using TB = Tile<BN, B_KC, NT, BKT>;
+    using TA = Tile<BM, A_KC, NT, BKT, true>;
+    using TB = Tile<BN, B_KC, NT, BKT, true>;
     constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
     static_assert(NST == 4, "the B fragments alternate between two slots by stage parity");
     static_assert((NST - 2) * NVM < 64, "vmcnt field");
@@ -1331,8 +1340,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_mfma_persist16_kernel(GemmP
     constexpr int HM = FM / 2;
     constexpr int NDS_A = A_KC ? HM : 2 * HM;                           // LDS reads of half the A fragments
     constexpr int NDS_B = B_KC ? FN : 2 * FN;                           // ... of all B fragments
-    using TA = Tile<BM, A_KC, NT, BKT>;
-    using TB = Tile<BN, B_KC, NT, BKT>;
+    using TA = Tile<BM, A_KC, NT, BKT, true>;
+    using TB = Tile<BN, B_KC, NT, BKT, true>;
     constexpr int NVM = TA::PER_THREAD + TB::PER_THREAD;
     constexpr int WAIT_KEEP = (NST - 2) * NVM;
     static_assert(NST == 4, "written for four stages");
@@ -1544,8 +1553,8 @@ template <bool A_KC, bool B_KC, bool F32_B>
 __global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int tn, int order) {
     constexpr int BM = 128, BN = 128, WN = 2, NT = 256, BKT = 32;
     constexpr int TM = 64, TN = 64, FM = 4, FN = 4;   // 16 x 16 blocks of v_mfma_f32_16x16x32_bf16 (one per 32-deep stage)
-    using TA = Tile<BM, A_KC, NT, BKT>;
-    using TB = Tile<BN, B_KC, NT, BKT>;
+    using TA = Tile<BM, A_KC, NT, BKT, true>;
+    using TB = Tile<BN, B_KC, NT, BKT, true>;
     using TF = std::conditional_t<F32_B, TB, TA>;   // tile type of the fp32 operand
     using TH = std::conditional_t<F32_B, TA, TB>;   // ... of the bf16 operand
     static_assert(TA::BYTES == TB::BYTES, "square tile");
