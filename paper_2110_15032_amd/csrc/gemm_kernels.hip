@@ -278,12 +278,13 @@ __device__ inline void static_for(F&& f) {
 // the XCD re-linearisation
 int g_tile_order = 0;
 
-// Band height when the knob leaves it open.  Measured with the persistent kernel (TFLOP/s at band
-// 2 / 3 / 4): 8 tile-columns per shard 1157 / 1142 / 1151; 16 columns 1049 / 1133 / 1101 and, with 4
-// tile-rows only, 960 / 998 / 1004; 489 columns 625 / 648 / 644.  So 3, except for narrow shards.
-inline int tile_order_for(int tn) {
+// Band height when the knob leaves it open.  Measured with the persistent kernels, ms at band
+// 1 / 2 / 3 / 4 / 6 / 8 / 16: 32 x 8 tiles per shard (K = 4096) .815 / .809 / .805 / .812 / .828 / .844 / .932;
+// 32 x 16 tiles (K = 2048 per shard) .947 / .945 / .906 / .905 / .897 / .900 / 1.18; 4 x 489 tiles: 3 or 4.
+// So 2 for narrow shards, 6 for wide ones with enough tile-rows to fill whole bands, else 3.
+inline int tile_order_for(int tm, int tn) {
     if (g_tile_order & 0xFF) return g_tile_order;
-    return (g_tile_order & ~0xFF) | (tn <= 8 ? 2 : 3);
+    return (g_tile_order & ~0xFF) | (tn <= 8 ? 2 : tm >= 12 ? 6 : 3);
 }
 
 struct TileCoord {
@@ -1684,7 +1685,7 @@ int32_t launch_split(const GemmPlan& plan, int max_m, int max_n, hipStream_t st)
     else if (plan.a_kc) kern = gemm_split_kernel<true, false, F32_B>;
     else if (plan.b_kc) kern = gemm_split_kernel<false, true, F32_B>;
     else kern = gemm_split_kernel<false, false, F32_B>;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, tile_order_for(tn));
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, tile_order_for(tm, tn));
     return launch_status(__func__);
 }
 
@@ -1703,10 +1704,10 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
         if (grid > nblk) grid = (int)nblk;
         if constexpr (ODD >= 200)
             hipLaunchKernelGGL((gemm_mfma_persist16_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 200, EPI, OutT>), dim3((uint32_t)grid),
-                               dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
+                               dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tm, tn) & 0xFFFF, (int)nblk);
         else
             hipLaunchKernelGGL((gemm_mfma_persist_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 100, EPI, OutT>), dim3((uint32_t)grid),
-                               dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn) & 0xFFFF, (int)nblk);
+                               dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tm, tn) & 0xFFFF, (int)nblk);
         return launch_status(__func__);
     }
     void (*kern)(GemmPlan, int, int, int);
@@ -1714,7 +1715,7 @@ int32_t launch_mfma_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t 
     else if constexpr (ODD >= 50) kern = gemm_mfma_pipe16_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD - 50, EPI, OutT>;   // 16x16x32 instruction
     else if constexpr (ODD >= 3) kern = gemm_mfma_pipe_kernel<BM, BN, WM, WN, A_KC, B_KC, ODD, EPI, OutT>;   // ODD carries the stage count
     else kern = gemm_mfma_kernel<BM, BN, WM, WN, A_KC, B_KC, 0, EPI, OutT>;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tn));
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(WM * WN * 64), 0, st, plan, tm, tn, tile_order_for(tm, tn));
     return launch_status(__func__);
 }
 
