@@ -98,10 +98,12 @@ typedef __attribute__((address_space(1))) const void gbl_void;
 typedef __attribute__((address_space(1))) const char gbl_char;
 
 // LDS image of a KC tile: row-major [R][BKT], the 16-byte chunks of a row permuted by XOR with
-// kswz(row).  A ds_read_b128 serves 16 lanes (16 consecutive rows, one chunk column) per pass and
-// the LDS has 64 banks of 4 bytes, so those 16 chunks must fall in 16 different 16-byte bank groups:
+// kswz(row).  A ds_read_b128 serves 16 lanes per pass and the LDS has 64 banks of 4 bytes, so the 16
+// chunks of a pass must fall in 16 different 16-byte bank groups.  The 32x32x16 fragments put 32
+// consecutive rows of one chunk column on lanes 0-31:
 //   BKT = 64 (128-byte rows): XOR with (row ^ row >> 3) & 7, BKT = 32 (64-byte rows): (row >> 2) & 3.
-// Both measured conflict-free on gfx950 (SQ_LDS_BANK_CONFLICT = 0).
+// Both measured conflict-free on gfx950 (SQ_LDS_BANK_CONFLICT = 0), whichever 16 lanes make a pass
+// (see kswz16 for the lane sets that the measurements point to).
 template <int BKT>
 __device__ inline int kswz(int row) {
     if constexpr (BKT == 64) return (row ^ (row >> 3)) & 7;
