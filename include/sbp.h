@@ -241,8 +241,9 @@ enum {
                                    32-deep stages, 7 = 6 on the 16x16x32 matrix instruction,
                                    12 = 6 as one persistent workgroup per compute unit
                                    (needs every local reduction length to be a multiple of 128), 16 =
-                                   12 on the 16x16x32 matrix instruction; a forced kernel that cannot
-                                   take the shapes gives SBP_ERR_UNSUPPORTED                           */
+                                   12 on the 16x16x32 matrix instruction, 21 = 16 with the two waves of
+                                   every SIMD taking turns at the matrix pipe (ping-pong); a forced
+                                   kernel that cannot take the shapes gives SBP_ERR_UNSUPPORTED        */
     SBP_KNOB_TILE_ORDER = 1     /* order in which workgroups walk output tiles: low byte = tile-rows per
                                    band (0, the default: chosen from the shape), bit 8 set = no per-XCD
                                    re-linearisation                                                     */

@@ -76,6 +76,11 @@ struct GemmPlan {
 
 int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream);
 void set_tile_order(int32_t order);
+// The ping-pong persistent kernel (gemm_pingpong_kernel.hip).  The caller has checked: bf16 operands, every
+// local reduction length a multiple of 128, operand row pitches of 16 bytes.  order: tile walk (see map_tile).
+int32_t launch_gemm_pingpong(const GemmPlan& plan, int max_m, int max_n, int order, hipStream_t stream);
+// Compute units of the current device, asked of the runtime once per device and kept.
+int compute_units();
 
 // ---------------------------------------------------------------------------------------------
 // Row statistics of the model-parallel softmax.
