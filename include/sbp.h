@@ -142,7 +142,10 @@ int32_t sbp_matmul_rowmax(const sbp_tensor_t* x, sbp_t sbp_x, const sbp_tensor_t
  *                           the identity.
  * in->rows/cols/dtype must equal out's; P tensors must be SBP_F32; reductions are
  * done in fp32 in shard order i = 0 .. k-1, so every B copy is bit-identical and
- * runs are bit-reproducible.  S/B -> S/B moves raw words and never interprets
+ * runs are bit-reproducible.  P(max), here and in the row maxima below: a NaN next
+ * to a number is ignored, and the maximum of +0 and -0 may carry either sign.  When
+ * every operand is NaN, sbp_boxing gives NaN; sbp_row_max and sbp_matmul_rowmax start
+ * from the identity and give -inf.  S/B -> S/B moves raw words and never interprets
  * them (NaN patterns survive).  trans must be 0 on both sides. */
 int32_t sbp_boxing(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t* out, sbp_t sbp_out,
                    int32_t k, void* stream);
@@ -189,10 +192,13 @@ int32_t sbp_boxing_cast(const sbp_tensor_t* in, sbp_t sbp_in, const sbp_tensor_t
  *   dtype rules as for sbp_matmul (a tensor with P(sum) in either position is SBP_F32).
  * sbp_boxing_2d: boxing along ONE grid axis; the other entry of the signature must stay.
  *   Inner entry changes: every group re-arranges its own tensor.  Outer entry changes: the
- *   devices with equal inner index b are boxed among themselves (they hold the whole tensor
- *   when the inner entry is B or P, slice b of it when the inner entry is S(d) and neither outer
- *   entry is S(d); an outer conversion along the inner split's own axis is SBP_ERR_UNSUPPORTED,
- *   as is changing both entries in one call).  Every part is validated before any is enqueued. */
+ *   devices with equal inner index b are boxed among themselves (with inner entry B they hold the
+ *   whole tensor under the outer signature, with inner entry P(op) one op-term of it, with inner
+ *   entry S(d) slice b of it provided neither outer entry is S(d)).  SBP_ERR_UNSUPPORTED: an outer
+ *   conversion along the inner split's own axis; reducing an outer P(op) while the inner entry is a
+ *   partial of the OTHER operation (the signature means outer-op over groups of inner-op over
+ *   devices, and sum and max do not commute); changing both entries in one call.  Every part is
+ *   validated before any is enqueued. */
 int32_t sbp_infer_matmul_2d(const sbp_t* sbp_x, const sbp_t* sbp_w, sbp_t* sbp_y);
 int32_t sbp_local_shape_2d(int64_t rows, int64_t cols, const sbp_t* sbp, int32_t k0, int32_t k1,
                            int32_t a, int32_t b, int64_t* local_rows, int64_t* local_cols);
@@ -244,10 +250,16 @@ enum {
                                    12 on the 16x16x32 matrix instruction, 21 = 16 with the two waves of
                                    every SIMD taking turns at the matrix pipe (ping-pong); a forced
                                    kernel that cannot take the shapes gives SBP_ERR_UNSUPPORTED        */
-    SBP_KNOB_TILE_ORDER = 1     /* order in which workgroups walk output tiles: low byte = tile-rows per
+    SBP_KNOB_TILE_ORDER = 1,    /* order in which workgroups walk output tiles: low byte = tile-rows per
                                    band (0, the default: chosen from the shape), bit 8 set = no per-XCD
                                    re-linearisation                                                     */
+    SBP_KNOB_BOX_REDUCE = 2     /* 16-byte vectors per lane in the reductions of sbp_boxing: 0 = chosen
+                                   from the size, 1 / 2 / 4 / 8, or 16 = the kernel that reads the k
+                                   sources out of phase (4, 8 or 16 sources; 8 per lane otherwise).  The
+                                   sums are the same bit for bit under every value.                     */
 };
+/* The knobs are process-wide settings read at every call (atomically); a caller that changes one while
+ * another thread is inside the library gets either value for that call.  They are meant for measurement. */
 int32_t sbp_set_knob(int32_t knob, int32_t value);
 
 /* Static, NUL-terminated description of a status code. */

@@ -61,12 +61,19 @@ void orc_reduce_sum(const double* const* parts, int32_t k, double* out, int64_t 
     }
 }
 
+/* max of two values under the reading taken for P(max) (the paper names the operation only): a NaN is
+ * ignored next to a number, NaN results only when both are NaN; of +0 and -0 the first one stays. */
+static double max_ignoring_nan(double s, double x) {
+    if (s != s) return x;
+    return x > s ? x : s;
+}
+
 /* out[e] = max_i parts[i][e] */
 void orc_reduce_max(const double* const* parts, int32_t k, double* out, int64_t n) {
 #pragma omp parallel for schedule(static)
     for (int64_t e = 0; e < n; ++e) {
         double s = parts[0][e];
-        for (int32_t i = 1; i < k; ++i) s = parts[i][e] > s ? parts[i][e] : s;
+        for (int32_t i = 1; i < k; ++i) s = max_ignoring_nan(s, parts[i][e]);
         out[e] = s;
     }
 }
@@ -82,7 +89,7 @@ void orc_row_max(const double* L, int64_t rows, int64_t cols, double* m) {
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
         double v = L[r * cols];
-        for (int64_t c = 1; c < cols; ++c) v = L[r * cols + c] > v ? L[r * cols + c] : v;
+        for (int64_t c = 1; c < cols; ++c) v = max_ignoring_nan(v, L[r * cols + c]);
         m[r] = v;
     }
 }

@@ -258,7 +258,8 @@ def boxing2(shards: list[np.ndarray], sbp_in2, sbp_out2, k0: int, k1: int) -> li
     Outer position: the devices with the same inner index b hold, between
     them, one tensor under the outer signature (the whole tensor when inner is
     B or P, its b-th slice when inner is S and the outer conversion leaves that
-    axis alone); each such group is boxed on its own."""
+    axis alone); each such group is boxed on its own.  An outer P(op) is not
+    reduced while the inner position is a partial of the OTHER operation."""
     assert len(shards) == k0 * k1
     if sbp_in2[0] == sbp_out2[0]:
         out = []
@@ -270,6 +271,12 @@ def boxing2(shards: list[np.ndarray], sbp_in2, sbp_out2, k0: int, k1: int) -> li
     inner = sbp_in2[1]
     if inner in (S0, S1) and inner in (sbp_in2[0], sbp_out2[0]):
         raise ValueError("outer boxing along the axis the inner position splits is not a per-slice operation")
+    # The nested signature means outer-op over the nodes of (inner-op over a node's devices) (Sec. 3.3:
+    # the outer entry places the tensor on the nodes, the inner entry each node's tensor on its devices).
+    # Reducing the outer partial first, device by device, would compute inner-op of outer-op instead,
+    # and sum and max do not commute.
+    if inner in (P_SUM, P_MAX) and sbp_in2[0] in (P_SUM, P_MAX) and sbp_in2[0] != inner:
+        raise ValueError("an outer partial cannot be reduced underneath an inner partial of another operation")
     out = [None] * (k0 * k1)
     for b in range(k1):
         plane = boxing([shards[a * k1 + b] for a in range(k0)], sbp_in2[0], sbp_out2[0], k0)

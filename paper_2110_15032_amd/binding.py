@@ -121,6 +121,16 @@ def _stream_ptr(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(stream)
 
 
+def _need(k: int, *tensors) -> None:
+    """The library reads k pointers from every shard array it is given: refuse here, before the call,
+    a tensor that holds fewer (a count the library itself rejects is left to the library)."""
+    if not 1 <= k <= 64:
+        return
+    for t in tensors:
+        if t is not None and t.k < k:
+            raise ValueError(f"tensor holds {t.k} shard pointers, the call needs {k}")
+
+
 def _check(status: int, what: str) -> None:
     if status != 0:
         raise SbpError(status, what)
@@ -144,31 +154,38 @@ def sbp_local_shape(rows: int, cols: int, sbp: int, k: int, i: int) -> tuple[int
 
 def sbp_matmul(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTensor, sbp_y: int, k: int,
                stream=None) -> None:
+    _need(k, x, w, y)
     _check(lib().sbp_matmul(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, k, _stream_ptr(stream)), "sbp_matmul")
 
 
 def sbp_matmul_ex(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTensor, sbp_y: int, k: int,
                   stream=None, epilogue: int = EPI_NONE) -> None:
+    _need(k, x, w, y)
     _check(lib().sbp_matmul_ex(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, k, _stream_ptr(stream), epilogue),
            "sbp_matmul_ex")
 
 
 def sbp_matmul_rowmax(x: SbpTensor, sbp_x: int, w: SbpTensor, sbp_w: int, y: SbpTensor, sbp_y: int, rowmax: SbpTensor,
                       k: int, stream=None) -> None:
+    _need(k, x, w, y, rowmax)
     _check(lib().sbp_matmul_rowmax(x.ref(), sbp_x, w.ref(), sbp_w, y.ref(), sbp_y, rowmax.ref(), k, _stream_ptr(stream)),
            "sbp_matmul_rowmax")
 
 
 def sbp_boxing(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
+    _need(k, inp, out)
     _check(lib().sbp_boxing(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing")
 
 
 def sbp_boxing_across(inp: SbpTensor, sbp_in: int, k_in: int, out: SbpTensor, sbp_out: int, k_out: int, stream=None) -> None:
+    _need(k_in, inp)
+    _need(k_out, out)
     _check(lib().sbp_boxing_across(inp.ref(), sbp_in, k_in, out.ref(), sbp_out, k_out, _stream_ptr(stream)),
            "sbp_boxing_across")
 
 
 def sbp_boxing_cast(inp: SbpTensor, sbp_in: int, out: SbpTensor, sbp_out: int, k: int, stream=None) -> None:
+    _need(k, inp, out)
     _check(lib().sbp_boxing_cast(inp.ref(), sbp_in, out.ref(), sbp_out, k, _stream_ptr(stream)), "sbp_boxing_cast")
 
 
@@ -190,32 +207,38 @@ def sbp_local_shape_2d(rows: int, cols: int, sbp2, k0: int, k1: int, a: int, b: 
 
 
 def sbp_matmul_2d(x: SbpTensor, sbp_x, w: SbpTensor, sbp_w, y: SbpTensor, sbp_y, k0: int, k1: int, stream=None) -> None:
+    _need(k0 * k1, x, w, y)
     sy = _pair(sbp_y) if sbp_y is not None else None
     _check(lib().sbp_matmul_2d(x.ref(), _pair(sbp_x), w.ref(), _pair(sbp_w), y.ref(), sy, k0, k1, _stream_ptr(stream)),
            "sbp_matmul_2d")
 
 
 def sbp_boxing_2d(inp: SbpTensor, sbp_in, out: SbpTensor, sbp_out, k0: int, k1: int, stream=None) -> None:
+    _need(k0 * k1, inp, out)
     _check(lib().sbp_boxing_2d(inp.ref(), _pair(sbp_in), out.ref(), _pair(sbp_out), k0, k1, _stream_ptr(stream)),
            "sbp_boxing_2d")
 
 
 def sbp_row_max(logits: SbpTensor, sbp_l: int, out: SbpTensor, k: int, stream=None) -> None:
+    _need(k, logits, out)
     _check(lib().sbp_row_max(logits.ref(), sbp_l, out.ref(), k, _stream_ptr(stream)), "sbp_row_max")
 
 
 def sbp_row_sumexp(logits: SbpTensor, sbp_l: int, gmax: SbpTensor, out: SbpTensor, k: int, stream=None) -> None:
+    _need(k, logits, gmax, out)
     _check(lib().sbp_row_sumexp(logits.ref(), sbp_l, gmax.ref(), out.ref(), k, _stream_ptr(stream)), "sbp_row_sumexp")
 
 
 def sbp_xent_loss(logits: SbpTensor, sbp_l: int, labels: SbpTensor, gmax: SbpTensor, denom: SbpTensor, loss: SbpTensor,
                   k: int, stream=None) -> None:
+    _need(k, logits, labels, gmax, denom, loss)
     _check(lib().sbp_xent_loss(logits.ref(), sbp_l, labels.ref(), gmax.ref(), denom.ref(), loss.ref(), k,
                                _stream_ptr(stream)), "sbp_xent_loss")
 
 
 def sbp_xent_grad(logits: SbpTensor, sbp_l: int, labels: SbpTensor, gmax: SbpTensor, denom: SbpTensor, grad: SbpTensor,
                   dlogits: SbpTensor, k: int, stream=None) -> None:
+    _need(k, logits, labels, gmax, denom, grad, dlogits)
     _check(lib().sbp_xent_grad(logits.ref(), sbp_l, labels.ref(), gmax.ref(), denom.ref(), grad.ref(), dlogits.ref(), k,
                                _stream_ptr(stream)), "sbp_xent_grad")
 

@@ -23,6 +23,7 @@
 //
 // HBM-bound: every input byte is read once and every output byte written once, with the widest
 // vector (up to 16 B per lane) that all offsets and pitches of the conversion allow.
+#include <atomic>
 #include <cstdlib>
 
 #include "sbp_internal.h"
@@ -190,6 +191,50 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t idx = base + u * stride;
+                if (idx < total) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[T.d0 + j]) + dpos[u]);
+            }
+        }
+    }
+}
+
+// The same reduction with the k source streams out of phase.  Equally sized shard buffers allocated one after
+// the other put equal offsets of all k sources on the same memory channel and bank, and the plain kernel asks for
+// exactly those k lines at once.  Here a lane owns KS vectors 4 KB apart and vector u takes source s - u in time
+// slice s (s = 0 .. 2 KS - 2): every vector still receives its sources in shard order 0 .. KS - 1 (same sums, bit
+// for bit), but the KS loads of one slice go to KS different offsets.
+template <typename V, int OP, int KS>
+__global__ __launch_bounds__(BOX_THREADS) void box_reduce_diag_kernel(BoxParams p) {
+    const Task T = make_task(p, blockIdx.y);
+    const uint32_t cols_v = (uint32_t)(T.cols / p.vec_elems);
+    const uint32_t total = (uint32_t)T.rows * cols_v;
+    const int64_t src_ld_v = T.src_ld / p.vec_elems, dst_ld_v = T.dst_ld / p.vec_elems;
+    const int64_t src_off_v = T.src_off / p.vec_elems, dst_off_v = T.dst_off / p.vec_elems;
+    for (uint32_t base = blockIdx.x * BOX_THREADS * KS + threadIdx.x; base < total; base += gridDim.x * BOX_THREADS * KS) {
+        V acc[KS];
+        int64_t spos[KS], dpos[KS];
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
+            uint32_t idx = base + u * BOX_THREADS;
+            idx = idx < total ? idx : total - 1;      // clamped: loaded, never stored
+            const uint32_t r = T.rows == 1 ? 0 : idx / cols_v;
+            const uint32_t c = idx - r * cols_v;
+            spos[u] = src_off_v + (int64_t)r * src_ld_v + c;
+            dpos[u] = dst_off_v + (int64_t)r * dst_ld_v + c;
+        }
+#pragma unroll
+        for (int s = 0; s < 2 * KS - 1; ++s) {
+#pragma unroll
+            for (int u = 0; u < KS; ++u) {
+                const int i = s - u;
+                if (i < 0 || i >= KS) continue;
+                const V v = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos[u]);
+                acc[u] = i == 0 ? v : combine<OP>(acc[u], v);
+            }
+        }
+        for (int j = 0; j < T.nd; ++j) {
+#pragma unroll
+            for (int u = 0; u < KS; ++u) {
+                const uint32_t idx = base + u * BOX_THREADS;
                 if (idx < total) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[T.d0 + j]) + dpos[u]);
             }
         }
@@ -511,10 +556,19 @@ void launch_reduce_k(const BoxParams& p, dim3 grid, hipStream_t st) {
     }
 }
 
+// 0 = chosen from the size (see launch_boxing); 1 / 2 / 4 / 8 = that many vectors per lane in box_reduce_kernel;
+// 16 = box_reduce_diag_kernel where it exists (4, 8 or 16 sources), else 8 vectors per lane
+std::atomic<int> g_box_reduce_variant{0};
+
 template <int OP>
 void launch_reduce(const BoxParams& p, dim3 grid, int unroll, hipStream_t st) {
     if (p.vec_elems == 4) {
-        if (unroll == 8) launch_reduce_k<f32x4, OP, 8>(p, grid, st);
+        if (unroll == 16 && p.ki == 8) hipLaunchKernelGGL((box_reduce_diag_kernel<f32x4, OP, 8>), grid, dim3(BOX_THREADS), 0, st, p);
+        else if (unroll == 16 && p.ki == 4) hipLaunchKernelGGL((box_reduce_diag_kernel<f32x4, OP, 4>), grid, dim3(BOX_THREADS), 0, st, p);
+        else if (unroll == 16 && p.ki == 16) hipLaunchKernelGGL((box_reduce_diag_kernel<f32x4, OP, 16>), grid, dim3(BOX_THREADS), 0, st, p);
+        else if (unroll >= 8) launch_reduce_k<f32x4, OP, 8>(p, grid, st);
+        else if (unroll == 4) launch_reduce_k<f32x4, OP, 4>(p, grid, st);
+        else if (unroll == 2) launch_reduce_k<f32x4, OP, 2>(p, grid, st);
         else launch_reduce_k<f32x4, OP, 1>(p, grid, st);
     } else if (p.vec_elems == 2) launch_reduce_k<f32x2, OP, 1>(p, grid, st);
     else launch_reduce_k<float, OP, 1>(p, grid, st);
@@ -662,16 +716,29 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
             return launch_status(__func__);
         }
     }
-    // Reductions of at most 32 MiB per source do better with eight consecutive vectors per lane (8 x 16 MiB
-    // all-reduce: 49.5 us against 52.5 us with four and 54.7 us with one; reduce-scatter 29.2 / 30.5 / 31.8 us),
-    // large ones with one (8 x 128 MiB: 365 us, against 378 us with four and 386 us with eight).
-    const int unroll = (reduce && vbytes == 16 && max_units <= ((int64_t)1 << 21)) ? 8 : 1;
+    // Vectors per lane of a reduction (16-byte vectors).  Measured on 8 sources, all-reduce, TB/s on buffers from
+    // separate allocations / carved back to back from one allocation / the same with 4 KiB between them:
+    //   8 x 128 MiB:  1 vector 5.76 / 4.57 / 5.59,  2: 5.18 / 5.30 / 5.55,  4: 5.61 / 5.47 / 5.58,  8: 5.43 / 5.43 / 5.40
+    //   8 x 16 MiB:   1: 4.55 / 4.48 / 4.74,  4: 4.91 / 4.89 / 5.37,  8: 5.19 / 5.03 / 5.30,  sources out of phase
+    //                 (box_reduce_diag_kernel): 5.36 / 5.26 / 5.43
+    // One vector per lane is the fastest on large tensors unless the k buffers lie back to back (equal offsets then
+    // share a memory bank, and the k stores of a lane hit it in a row); four lose 3 % there and hold up on every
+    // layout, so four it is.  Small tensors (up to 32 MiB per source) take the out-of-phase kernel where it exists.
+    int unroll = 1;
+    if (reduce && vbytes == 16) {
+        const bool small = max_units <= ((int64_t)1 << 21);
+        const bool diag = p.mode != M_P2P && (p.ki == 4 || p.ki == 8 || p.ki == 16);
+        unroll = small ? (diag ? 16 : 8) : 4;
+        const int forced = g_box_reduce_variant.load(std::memory_order_relaxed);
+        if (forced) unroll = (forced == 16 && !diag) ? 8 : forced;
+    }
+    const int per_lane = unroll == 16 ? p.ki : unroll;
     // Workgroups in the whole grid, at most.  A copy workgroup that moves a single 4 KB piece costs more to
     // start than to run: with 131072 of them a 2 x 512 MiB relayout ran at 3.2-4.7 TB/s, with 32768 (four
     // pieces each, grid-stride) at 5.4-6.0, and 2 x 1 GiB went from 5.5-5.7 to 5.8-5.9; 8192 is slower
     // again.  Reductions issue k loads per vector and are indifferent between 32768 and 65536.
     const int64_t cap_total = reduce ? 65536 : 32768;
-    int64_t bx = (max_units + (int64_t)BOX_THREADS * unroll - 1) / ((int64_t)BOX_THREADS * unroll);
+    int64_t bx = (max_units + (int64_t)BOX_THREADS * per_lane - 1) / ((int64_t)BOX_THREADS * per_lane);
     const int64_t cap = (cap_total + tasks - 1) / tasks;
     if (bx > cap) bx = cap;
     if (bx < 1) bx = 1;
@@ -689,6 +756,8 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     }
     return launch_status(__func__);
 }
+
+void set_box_reduce_variant(int32_t v) { g_box_reduce_variant.store(v, std::memory_order_relaxed); }
 
 int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream) {
     BoxParams p{};

@@ -277,12 +277,13 @@ constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 // Row maximum of stored results (model-parallel softmax, Sec. 6.3.1, fused into the logits GEMM):
 // max over fp32 bit patterns with one integer atomic, signed max for non-negative values and unsigned
 // min for negative ones (both orders agree with the float order on their half; -0 is folded to +0
-// first).  Issued as inline assembly like the other stores of the persistent kernel.  The target
-// starts at -inf (fill_rowmax_kernel).
+// first; a NaN matches neither and is ignored, as fmaxf ignores it in the two-pass form).  Issued as
+// inline assembly like the other stores of the persistent kernel.  The target starts at -inf
+// (fill_rowmax_kernel).
 __device__ inline void atomic_max_f32_untracked(float* a, float v) {
     v += 0.0f;
     if (v >= 0.0f) asm volatile("global_atomic_smax %0, %1, off" : : "v"(a), "v"(v) : "memory");
-    else asm volatile("global_atomic_umin %0, %1, off" : : "v"(a), "v"(v) : "memory");
+    else if (v < 0.0f) asm volatile("global_atomic_umin %0, %1, off" : : "v"(a), "v"(v) : "memory");   // a NaN is ignored
 }
 
 // 16-byte streaming store the compiler does not track.  The two idle cycles cover the hardware's

@@ -77,15 +77,16 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmPlan p) {
 
 // tile walk: low byte = tile-rows per band (0 = chosen from the shape, see tile_order_for), bit 8 = skip
 // the XCD re-linearisation
-int g_tile_order = 0;
+std::atomic<int> g_tile_order{0};
 
 // Band height when the knob leaves it open.  Measured with the persistent kernels, ms at band
 // 1 / 2 / 3 / 4 / 6 / 8 / 16: 32 x 8 tiles per shard (K = 4096) .815 / .809 / .805 / .812 / .828 / .844 / .932;
 // 32 x 16 tiles (K = 2048 per shard) .947 / .945 / .906 / .905 / .897 / .900 / 1.18; 4 x 489 tiles: 3 or 4.
 // So 2 for narrow shards, 6 for wide ones with enough tile-rows to fill whole bands, else 3.
 inline int tile_order_for(int tm, int tn) {
-    if (g_tile_order & 0xFF) return g_tile_order;
-    return (g_tile_order & ~0xFF) | (tn <= 8 ? 2 : tm >= 12 ? 6 : 3);
+    const int knob = g_tile_order.load(std::memory_order_relaxed);
+    if (knob & 0xFF) return knob;
+    return (knob & ~0xFF) | (tn <= 8 ? 2 : tm >= 12 ? 6 : 3);
 }
 
 
@@ -1505,7 +1506,7 @@ bool pingpong_pays(const GemmPlan& plan, int max_m, int max_n) {
 
 }  // namespace
 
-void set_tile_order(int32_t order) { g_tile_order = order; }
+void set_tile_order(int32_t order) { g_tile_order.store(order, std::memory_order_relaxed); }
 
 int compute_units() {
     constexpr int MAX_DEV = 64;

@@ -235,8 +235,7 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
                         float* dst = ot.rowmax + (IP / 2) * 64 + ln;
                         // signed max for non-negative values, unsigned min for negative ones (see atomic_max_f32_untracked);
                         // both instructions always issue (the wait counts rely on it), each under its own lanes
-                        const bool pos = vmax >= 0.0f;
-                        const uint64_t mp = __builtin_amdgcn_ballot_w64(pos), mn = __builtin_amdgcn_ballot_w64(!pos);
+                        const uint64_t mp = __builtin_amdgcn_ballot_w64(vmax >= 0.0f), mn = __builtin_amdgcn_ballot_w64(vmax < 0.0f);   // NaN: neither
                         asm volatile("s_mov_b64 exec, %2\n\tglobal_atomic_smax %0, %1, off\n\ts_mov_b64 exec, %3\n\tglobal_atomic_umin %0, %1, off\n\ts_mov_b64 exec, -1"
                                      : : "v"(dst), "v"(vmax), "s"(mp), "s"(mn) : "memory");
                     }

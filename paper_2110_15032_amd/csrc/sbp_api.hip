@@ -132,6 +132,10 @@ int32_t sbp_set_knob(int32_t knob, int32_t value) {
         set_tile_order(value);
         return SBP_OK;
     }
+    if (knob == SBP_KNOB_BOX_REDUCE && (value == 0 || value == 1 || value == 2 || value == 4 || value == 8 || value == 16)) {
+        set_box_reduce_variant(value);
+        return SBP_OK;
+    }
     return SBP_ERR_UNSUPPORTED;
 }
 
@@ -457,6 +461,10 @@ int32_t sbp_boxing_2d(const sbp_tensor_t* in, const sbp_t* s_in, const sbp_tenso
     // outer conversion with an inner split: the devices of inner index b hold slice b of the tensor
     // only if the conversion does not touch the axis the inner position splits
     if (!inner && (keep == SBP_S(0) || keep == SBP_S(1)) && (s_in[0] == keep || s_out[0] == keep)) return SBP_ERR_UNSUPPORTED;
+    // (outer, inner) stands for outer-op over the groups of (inner-op over a group's devices): an outer partial
+    // reduced device by device underneath an inner partial of the OTHER operation would swap the two reductions,
+    // and sum and max do not commute
+    if (!inner && is_partial(keep) && is_partial(s_in[0]) && s_in[0] != keep) return SBP_ERR_UNSUPPORTED;
 
     std::vector<Span> ins, outs;
     spans_of2(in, s_in, k0, k1, ins);

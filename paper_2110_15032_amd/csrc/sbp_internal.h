@@ -46,6 +46,7 @@ struct BoxPlan {
 };
 
 int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream);
+void set_box_reduce_variant(int32_t v);
 // fp32 S(a) -> bf16 B (cast + all-gather) and bf16 P(sum) -> fp32 S(a) (cast + reduce-scatter); elem_bytes unused
 int32_t launch_boxing_cast(const BoxPlan& plan, hipStream_t stream);
 

@@ -90,6 +90,45 @@ def test_partial_value_boxing(k, op, so):
                 assert_bits_equal(got[j], got[0], f"B copies 0 and {j} of P({op})->B")
 
 
+@pytest.mark.parametrize("so", [orc.B, orc.S0])
+def test_partial_max_with_nan_and_signed_zero(so):
+    """P(max) ignores a NaN next to a number, gives NaN only when every partial is NaN, and may give either
+    sign for the maximum of +0 and -0 (the reading in sbp.h; the oracle takes the same one)."""
+    k, shape = 3, (8, 64)
+    nan = np.float32("nan")
+    parts = [rnd_f32(900 + i, shape) for i in range(k)]
+    parts[0][0, :8] = nan                      # NaN first, numbers after
+    parts[2][1, :8] = nan                      # numbers first, NaN last
+    for q in parts:
+        q[2, :8] = nan                         # all NaN
+    parts[0][3, :8], parts[1][3, :8], parts[2][3, :8] = 0.0, -0.0, -0.0
+    parts[0][4, :8], parts[1][4, :8], parts[2][4, :8] = -0.0, -1.0, 0.0
+    ref = orc.boxing(parts, orc.P_MAX, so, k)
+    d_in = DevTensor.from_host(parts, *shape, orc.P_MAX)
+    d_out = DevTensor.empty(*shape, np.float32, so, k)
+    sbp.sbp_boxing(d_in.desc, sbp.P_MAX, d_out.desc, TO_ABI[so], k)
+    sync()
+    for j, (g, r) in enumerate(zip(d_out.host(), ref)):
+        r = r.astype(np.float32)
+        assert np.array_equal(np.isnan(g), np.isnan(r)), f"NaN positions, shard {j}"
+        ok = ~np.isnan(r)
+        assert np.array_equal(g[ok], r[ok]), f"values, shard {j}"           # -0 == +0 here: either sign passes
+        nz = ok & (r != 0)
+        assert np.array_equal(g[nz].view(np.uint32), r[nz].view(np.uint32)), f"bits, shard {j}"
+    # the local row maximum of the model-parallel softmax takes the same reading
+    L = rnd_f32(950, (16, 96))
+    L[0, 5], L[1, :], L[2, 0] = nan, nan, nan
+    Ls = orc.scatter(L, orc.S1, k)
+    d_l = DevTensor.from_host(Ls, 16, 96, orc.S1)
+    m_p = DevTensor.empty(16, 1, np.float32, orc.P_MAX, k)
+    sbp.sbp_row_max(d_l.desc, sbp.S(1), m_p.desc, k)
+    sync()
+    for i, g in enumerate(m_p.host()):
+        r = orc.row_max(Ls[i].astype(np.float64))[:, None].astype(np.float32)
+        r[np.isnan(r)] = -np.inf               # an all-NaN row: the kernel starts from the identity of max
+        assert np.array_equal(g, r), f"row max, shard {i}"
+
+
 @pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
 @pytest.mark.parametrize("op", ["sum", "max"])
 @pytest.mark.parametrize("si", [orc.S0, orc.S1, orc.B])

@@ -172,6 +172,8 @@ def test_2d_validation_errors():
     assert status_of(sbp.sbp_matmul_2d, x, (S0, B_), w, (B_, S1), x, None, k0, k1, st) == -7        # y over x
     assert status_of(sbp.sbp_boxing_2d, x, (S0, P), y, (B_, B_), k0, k1, st) == -9                  # both entries change
     assert status_of(sbp.sbp_boxing_2d, x, (S0, S0), y, (B_, S0), k0, k1, st) == -9                 # along the inner split's axis
+    assert status_of(sbp.sbp_boxing_2d, x, (P, sbp.P_MAX), y, (B_, sbp.P_MAX), k0, k1, st) == -9    # outer sum under an inner max
+    assert status_of(sbp.sbp_boxing_2d, x, (sbp.P_MAX, P), y, (S0, P), k0, k1, st) == -9            # outer max under an inner sum
     assert status_of(sbp.sbp_boxing_2d, fake(4, 8, 8, sbp.BF16), (S0, P), fake(4, 8, 8, sbp.BF16, base=0x30000000), (S0, B_), k0, k1, st) == -4
     assert status_of(sbp.sbp_boxing_2d, x, (S0, B_), x, (S0, S1), k0, k1, st) == -7
     assert sbp.sbp_infer_matmul_2d((S0, S1), (B_, S0)) == (S0, P)
@@ -258,3 +260,18 @@ def test_local_shapes_agree_with_the_oracle_on_random_geometry():
 
     one_d()
     two_d()
+
+
+def test_binding_refuses_a_shard_array_shorter_than_k():
+    """The library reads k pointers from every shard array; the binding must not let a short array through."""
+    x, w, y = fake(2, 8, 8), fake(2, 8, 8, base=0x20000000), fake(2, 8, 8, base=0x30000000)
+    with pytest.raises(ValueError):
+        sbp.sbp_matmul(x, sbp.S(0), w, sbp.B, y, sbp.S(0), 4, 0)
+    with pytest.raises(ValueError):
+        sbp.sbp_boxing(x, sbp.S(0), y, sbp.B, 3, 0)
+    with pytest.raises(ValueError):
+        sbp.sbp_boxing_across(x, sbp.S(0), 2, y, sbp.B, 5, 0)
+    with pytest.raises(ValueError):
+        sbp.sbp_boxing_2d(x, (sbp.S(0), sbp.B), y, (sbp.S(0), sbp.S(1)), 2, 2, 0)
+    # a count the library rejects by itself still reaches it
+    assert status_of(sbp.sbp_boxing, x, sbp.S(0), y, sbp.B, 65, 0) == -2

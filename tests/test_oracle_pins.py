@@ -450,3 +450,17 @@ def test_model_parallel_xent_is_the_plain_one_for_every_shard_count(k):
     assert np.array_equal(sum((p != 0).astype(int) for p in parts), (np.arange(R) != 5).astype(int))
     grads = orc.xent_grad_sbp(Ls, y, m, s, g)
     assert np.allclose(orc.assemble(grads, S1), orc.softmax_xent_grad(L, y, g), atol=1e-13)
+
+
+def test_partial_max_ignores_nan_next_to_a_number():
+    """Reading for P(max) and the row maximum (the paper names the operation only): a NaN counts as
+    missing, whatever its position; only all-NaN gives NaN.  numpy's fmax is that rule."""
+    nan = float("nan")
+    parts = [np.array([[nan, 1.0, -2.0, nan, -0.0]]), np.array([[3.0, nan, -5.0, nan, 0.0]]), np.array([[2.0, 0.5, nan, nan, -0.0]])]
+    got = orc.assemble(parts, orc.P_MAX)
+    want = np.fmax(np.fmax(parts[0], parts[1]), parts[2])
+    assert np.array_equal(got[:, :3], want[:, :3]) and np.array_equal(got[:, :3], np.array([[3.0, 1.0, -2.0]]))
+    assert np.isnan(got[0, 3]) and got[0, 4] == 0.0
+    L = np.array([[nan, -1.0, -3.0], [-7.0, nan, -6.0], [nan, nan, nan]])
+    m = orc.row_max(L)
+    assert m[0] == -1.0 and m[1] == -6.0 and np.isnan(m[2])

@@ -178,3 +178,27 @@ def test_boxing2_inner_all_reduce_of_table3_row2():
         block = T[slice(*orc.split_range(8, k0, a))]
         for b in range(k1):
             assert np.allclose(out[a * k1 + b], block, atol=1e-12)
+
+
+def test_boxing2_refuses_to_reduce_an_outer_partial_under_an_inner_partial_of_the_other_op():
+    """Sec. 3.3: (outer, inner) = outer-op over nodes of (inner-op over a node's devices).  With
+    X_ab on device (a, b), (P(sum), P(max)) stands for sum_a max_b X_ab; summing over a per device
+    would leave max_b sum_a X_ab, another tensor."""
+    k0, k1 = 2, 2
+    X = [np.array([[1.0]]), np.array([[5.0]]), np.array([[4.0]]), np.array([[2.0]])]   # X_00, X_01, X_10, X_11
+    glob = orc.assemble2(X, (P_SUM, orc.P_MAX), k0, k1)
+    assert glob.item() == max(1.0, 5.0) + max(4.0, 2.0) == 9.0
+    naive = max(1.0 + 4.0, 5.0 + 2.0)          # outer sum first, device by device: 7, not 9
+    assert naive != glob.item()
+    for outer_out in (B, S0, S1):
+        with pytest.raises(ValueError):
+            orc.boxing2(X, (P_SUM, orc.P_MAX), (outer_out, orc.P_MAX), k0, k1)
+        with pytest.raises(ValueError):
+            orc.boxing2(X, (orc.P_MAX, P_SUM), (outer_out, P_SUM), k0, k1)
+    # the inner position of the same signature may be reduced: every node takes its own max
+    inner = orc.boxing2(X, (P_SUM, orc.P_MAX), (P_SUM, B), k0, k1)
+    assert [x.item() for x in inner] == [5.0, 5.0, 4.0, 4.0]
+    assert orc.assemble2(inner, (P_SUM, B), k0, k1).item() == 9.0
+    # equal operations commute and stay allowed
+    same = orc.boxing2(X, (P_SUM, P_SUM), (B, P_SUM), k0, k1)
+    assert orc.assemble2(same, (B, P_SUM), k0, k1).item() == 12.0
