@@ -38,6 +38,14 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak, GB/s
 TRAFFIC_BYTES = {"gemm1": 1.858e9, "gemm2": 3.390e9, "boxing_p2b": 2.171e9}
 
 
+def shard_range(n, k, i):
+    """[begin, end) of shard i when n indices are split over k devices: the library's own balanced split
+    (sbp_local_shape), so that the harness holds no split rule of its own"""
+    import paper_2110_15032_amd as sbp
+    lens = [sbp.sbp_local_shape(n, 1, sbp.S(0), k, j)[0] for j in range(i + 1)]
+    return sum(lens[:-1]), sum(lens)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,8 +123,8 @@ def main():
     w1_sh = arena([(D, F // k)] * k, torch.int16)                                # [4096, 2048] each
     w2_sh = arena([(F // k, D)] * k, torch.int16)                                # [2048, 4096] each
     for i in range(k):
-        w1_sh[i].copy_(bf16_dev(cfg["W1"], cols=np.arange(*wl.split_range(F, k, i))))
-        w2_sh[i].copy_(bf16_dev(cfg["W2"], rows=np.arange(*wl.split_range(F, k, i))))
+        w1_sh[i].copy_(bf16_dev(cfg["W1"], cols=np.arange(*shard_range(F, k, i))))
+        w2_sh[i].copy_(bf16_dev(cfg["W2"], rows=np.arange(*shard_range(F, k, i))))
     h_sh = arena([(T, F // k)] * k, torch.int16)
     y_sh = arena([(T, D)] * k, torch.float32)
     yb_sh = arena([(T, D)] * k, torch.float32)
@@ -270,7 +278,7 @@ def bench_dp_grad(args, cfg, sbp, wl, torch, np):
         x_sh = arena([(Tk // k, Din)] * k, torch.int16)
         dy_sh = arena([(Tk // k, Dout)] * k, torch.int16)
         for i in range(k):
-            rows = np.arange(*wl.split_range(Tk, k, i))
+            rows = np.arange(*shard_range(Tk, k, i))
             for dst, spec in ((x_sh[i], cfg["X"]), (dy_sh[i], cfg["dY"])):
                 v = wl.normal(seed + r, spec["id"], spec["shape"], spec["dist"][1], rows, None, dtype=np.float32)
                 dst.copy_(torch.from_numpy(wl.to_bf16_bits(v).view(np.int16)))
@@ -322,7 +330,7 @@ def bench_classifier(args, cfg, sbp, wl, torch, np):
         t.copy_(f0)
     w_sh = arena([(Dm, Ci)] * k, torch.int16)
     for i in range(k):
-        w_sh[i].copy_(bits(cfg["W"], cols=np.arange(*wl.split_range(C, k, i))))
+        w_sh[i].copy_(bits(cfg["W"], cols=np.arange(*shard_range(C, k, i))))
     l_sh = arena([(R, Ci)] * k, torch.int16)
     vec = lambda: arena([(R, 1)] * k, torch.float32)      # noqa: E731
     Ft, Wt = sbp.SbpTensor(f_sh, R, Dm, sbp.BF16), sbp.SbpTensor(w_sh, Dm, C, sbp.BF16)
@@ -418,8 +426,8 @@ def bench_uvw(args, cfg, sbp, wl, torch, np):
     w_sh = arena([(N1, N2)] * k, torch.int16)
     w0 = bits(102, (N1, N2), 0.02)
     for i in range(k):
-        u_sh[i].copy_(bits(100, (M, K1), 1.0, cols=np.arange(*wl.split_range(K1, k, i))))
-        v_sh[i].copy_(bits(101, (K1, N1), 0.02, rows=np.arange(*wl.split_range(K1, k, i))))
+        u_sh[i].copy_(bits(100, (M, K1), 1.0, cols=np.arange(*shard_range(K1, k, i))))
+        v_sh[i].copy_(bits(101, (K1, N1), 0.02, rows=np.arange(*shard_range(K1, k, i))))
         w_sh[i].copy_(w0)
     U, V, W = sbp.SbpTensor(u_sh, M, K1, sbp.BF16), sbp.SbpTensor(v_sh, K1, N1, sbp.BF16), sbp.SbpTensor(w_sh, N1, N2, sbp.BF16)
     f32 = lambda r, c: sbp.SbpTensor(arena([(r, c)] * k, torch.float32), r, c, sbp.F32)      # noqa: E731
@@ -460,7 +468,7 @@ def bench_zero(args, cfg, sbp, wl, torch, np):
     arena = make_arena(torch, np, args.stagger)
     w32 = arena([(R // k, C)] * k, torch.float32)
     for i in range(k):
-        rows = np.arange(*wl.split_range(R, k, i))
+        rows = np.arange(*shard_range(R, k, i))
         w32[i].copy_(torch.from_numpy(wl.normal(wl.SEED_BASE, 200, (R, C), 0.02, rows, None, dtype=np.float32)))
     w16 = arena([(R, C)] * k, torch.int16)
     g16 = arena([(R, C)] * k, torch.int16)
@@ -597,13 +605,13 @@ def bench_tiny(args, cfg, sbp, wl, torch, np):
     [64,96]; boxing P(sum)->B and P(sum)->S(0).  Reported in microseconds per call."""
     k = cfg["k"]
     (M, K), N = cfg["X"]["shape"], cfg["W"]["shape"][1]
-    x = [torch.from_numpy(wl.uniform(wl.SEED_BASE, cfg["X"]["id"], (M, K), -1.0, 1.0, None, np.arange(*wl.split_range(K, k, i)))
+    x = [torch.from_numpy(wl.uniform(wl.SEED_BASE, cfg["X"]["id"], (M, K), -1.0, 1.0, None, np.arange(*shard_range(K, k, i)))
                           .astype(np.float32)).cuda().contiguous() for i in range(k)]
-    w = [torch.from_numpy(wl.uniform(wl.SEED_BASE, cfg["W"]["id"], (K, N), -1.0, 1.0, np.arange(*wl.split_range(K, k, i)), None)
+    w = [torch.from_numpy(wl.uniform(wl.SEED_BASE, cfg["W"]["id"], (K, N), -1.0, 1.0, np.arange(*shard_range(K, k, i)), None)
                           .astype(np.float32)).cuda().contiguous() for i in range(k)]
     y = [torch.empty(M, N, dtype=torch.float32, device="cuda") for _ in range(k)]
     yb = [torch.empty(M, N, dtype=torch.float32, device="cuda") for _ in range(k)]
-    ys = [torch.empty(wl.split_range(M, k, i)[1] - wl.split_range(M, k, i)[0], N, dtype=torch.float32, device="cuda") for i in range(k)]
+    ys = [torch.empty(shard_range(M, k, i)[1] - shard_range(M, k, i)[0], N, dtype=torch.float32, device="cuda") for i in range(k)]
     X, W = sbp.SbpTensor(x, M, K, sbp.F32), sbp.SbpTensor(w, K, N, sbp.F32)
     Y, YB, YS = (sbp.SbpTensor(t, M, N, sbp.F32) for t in (y, yb, ys))
 

@@ -429,7 +429,16 @@ def transfer_elems_across(sbp_in, k_in: int, sbp_out, k_out: int, rows: int, col
         inner = transfer_elems(S0, B, rows, cols, k_out)
         return transfer_elems_across(sbp_in, k_in, S0, k_out, rows, cols) + inner
     if sbp_in in (P_SUM, P_MAX) and sbp_out in (P_SUM, P_MAX):
-        return k_in * T                                # partial i travels whole, once, to device i mod k_out
+        # walk the routing with tagged partials: partial i is 2^i everywhere, so the value an output device ends
+        # up with spells out which partials it received; each of those travelled whole
+        assert k_in <= 52, "tags must stay exact in float64"
+        tagged = [np.full((rows, cols), float(1 << i)) for i in range(k_in)]
+        held = boxing_across(tagged, P_SUM, P_SUM, k_out)
+        moved = 0
+        for h in held:
+            assert (h == h.flat[0]).all(), "a partial arrives whole or not at all"
+            moved += bin(int(h.flat[0])).count("1") * T
+        return moved
     moved = 0
     probe = np.arange(T, dtype=np.float64).reshape(rows, cols) + 1.0   # no zeros: padding is visible
     held = boxing_across(scatter(probe, sbp_in, k_in) if sbp_in not in (P_SUM, P_MAX)

@@ -366,9 +366,12 @@ def test_matmul_gelu_epilogue_and_single_rounding():
     for i in range(k):
         ref = orc.bf16_to_f64(orc.bf16_round(orc.gelu(pre[i])))
         assert_matmul_close(values(got[i]), ref, 2e-2, f"gelu shard {i}")
-        # far tighter in fact: the bf16 result may differ from the oracle's by one rounding step
-        ulp = np.abs(values(got[i]) - ref) / np.maximum(np.abs(ref), 1e-30)
-        assert np.quantile(ulp, 0.999) <= 2.0 ** -7
+        # Far tighter in fact, for EVERY element: the kernel's gelu is within 2.2e-5 relative of the erf form and
+        # both sides round once, so the two bf16 results differ by at most one rounding step (2^-7 relative);
+        # the floor covers the fp32 accumulation order of the 128 products in front of it (values near zero).
+        err = np.abs(values(got[i]) - ref)
+        bound = 2.0 ** -7 * np.abs(ref) + 2e-5
+        assert (err <= bound).all(), f"gelu shard {i}: worst excess {np.max(err - bound):.3e} at ref {ref.flat[np.argmax(err - bound)]:.4e}"
 
 
 def test_empty_and_degenerate_shards():

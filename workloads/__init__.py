@@ -5,5 +5,5 @@ tensors.  Both the CPU oracle's tests and the HIP path's tests / bench take
 their inputs from here; neither the oracle nor the HIP package imports it.
 """
 from .generate import (SEED_BASE, normal, uniform, to_bf16_bits, bf16_bits_to_f32,  # noqa: F401
-                       pattern_u16, split_range)
+                       pattern_u16)
 from .configs import CONFIGS  # noqa: F401

@@ -96,9 +96,11 @@ def normal(seed: int, tensor_id: int, shape, std=1.0, rows=None, cols=None, dtyp
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """finite float values -> bfloat16 words (uint16), nearest / ties to even"""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    return ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+    """float values -> bfloat16 words (uint16): torch's own fp32 -> bf16 cast (nearest, ties to even), so
+    that this module holds no rounding arithmetic of its own"""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -111,11 +113,3 @@ def pattern_u16(shape, rows=None, cols=None) -> np.ndarray:
     r = np.asarray(r_idx, dtype=np.uint64)[:, None]
     c = np.asarray(c_idx, dtype=np.uint64)[None, :]
     return ((r * np.uint64(shape[1]) + c) & np.uint64(0xFFFF)).astype(np.uint16)
-
-
-def split_range(n: int, k: int, i: int) -> tuple[int, int]:
-    """index range a harness gives shard i when it cuts inputs into k pieces
-    (floor(n/k) each, the first n mod k pieces one longer)"""
-    q, r = divmod(n, k)
-    b = i * q + min(i, r)
-    return b, b + q + (1 if i < r else 0)
