@@ -262,6 +262,19 @@ enum {
  * another thread is inside the library gets either value for that call.  They are meant for measurement. */
 int32_t sbp_set_knob(int32_t knob, int32_t value);
 
+/* Diagnostic, not part of the method: a loop of matrix instructions alone, to measure what the chip's matrix
+ * pipes sustain and what operand fragment reads between the instructions cost (context for the rates that
+ * sbp_matmul reaches; bench.py --workload mfma_probe reports it).  One workgroup of 8 waves per compute unit;
+ * every wave runs `iters` rounds of 32 v_mfma_f32_16x16x32_bf16 (2 * 16 * 16 * 32 flop each per wave).
+ *   mode 0: matrix instructions only; 1: with 16 LDS fragment reads per round interleaved in both waves of a
+ *   SIMD and a barrier per round (lockstep schedule); 2: the two waves of a SIMD alternating between their
+ *   reads and their matrix instructions (ping-pong schedule).
+ *   zero_operands != 0: all-zero fragments instead of pseudo-random ones (no operand toggling).
+ *   scratch: 1 MiB of device memory, 16-byte aligned, caller-owned; after the call has completed its first
+ *   8 uint64 words hold the shader cycles each wave of workgroup 0 spent in the loop.
+ * Total flop of a call: compute units * 8 * iters * 32 * 16384. */
+int32_t sbp_probe_mfma(int32_t mode, int32_t iters, int32_t zero_operands, void* scratch, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* sbp_strerror(int32_t status);
 

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsbp_mi355x.so")
 
-SOURCES = ["sbp_api.hip", "boxing_kernels.hip", "gemm_kernels.hip", "gemm_pingpong_kernel.hip", "softmax_kernels.hip"]
+SOURCES = ["sbp_api.hip", "boxing_kernels.hip", "gemm_kernels.hip", "gemm_pingpong_kernel.hip", "softmax_kernels.hip", "probe_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -54,7 +54,7 @@ def build(extra_flags: list[str] | None = None, verbose: bool = False, out: str 
         obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
         return _compile(src, extra, obj)
 
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(one, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     subprocess.check_call(cmd)

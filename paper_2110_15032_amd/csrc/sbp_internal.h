@@ -82,6 +82,8 @@ void set_tile_order(int32_t order);
 int32_t launch_gemm_pingpong(const GemmPlan& plan, int max_m, int max_n, int order, hipStream_t stream);
 // Compute units of the current device, asked of the runtime once per device and kept.
 int compute_units();
+// Diagnostic matrix-pipe loop (probe_kernels.hip); scratch: 1 MiB of device memory.
+int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scratch, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
 // Row statistics of the model-parallel softmax.
