@@ -35,6 +35,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak, TFLOP/s
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak, GB/s
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
 # calibration copy; summary in profiles/bench_mlp_k8_counters.md).  Offline figures, not re-measured here.
+TRAFFIC_SOURCE = "constant from an earlier rocprofv3 --pmc run of this command (profiles/bench_mlp_k8_counters.md), not measured by this run"
 TRAFFIC_BYTES = {"gemm1": 1.858e9, "gemm2": 3.390e9, "boxing_p2b": 2.171e9}
 
 
@@ -55,8 +56,10 @@ def parse():
     ap.add_argument("--cpu-rows", type=int, default=4096, help="token rows in the oracle's sample")
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
     ap.add_argument("--tile-order", type=int, default=0, help="GEMM tile walk knob (0 = the library's choice)")
-    ap.add_argument("--stagger", type=int, default=4096, help="bytes of offset between consecutive shard buffers")
-    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe", "tiny", "grid"],
+    ap.add_argument("--layout", default="separate", choices=["separate", "contiguous", "staggered"],
+                    help="how the k shard buffers of a tensor lie in HBM: k allocations (default), back to back in one, or --stagger bytes apart in one")
+    ap.add_argument("--stagger", type=int, default=4096, help="bytes between consecutive shard buffers with --layout staggered")
+    ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe", "mfma_probe", "vendor_gemm", "tiny", "grid"],
                     help="mlp (default) is the workload the headline metric is quoted on")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
@@ -98,22 +101,10 @@ def main():
         x = wl.normal(seed, spec["id"], spec["shape"], spec["dist"][1], rows, cols, dtype=np.float32)
         return torch.from_numpy(wl.to_bf16_bits(x).view(np.int16)).to(dev)
 
-    # The k shard buffers of a tensor stand for memory on k different devices.  In one HBM, equal
-    # offsets in equally sized, back-to-back buffers fall on the same memory channel, which k real
-    # devices would not share; carving each tensor's shards from one arena with a 4 KiB stagger
-    # removes that artefact of the emulation (measured: 5.8 instead of 5.0-5.4 TB/s on the all-reduce).
-    STAGGER = args.stagger
-
-    def arena(shapes, dtype):
-        esz = torch.empty((), dtype=dtype).element_size()
-        sizes = [int(np.prod(sh)) for sh in shapes]
-        step = [((n * esz + STAGGER + 255) // 256 * 256) // esz for n in sizes]
-        buf = torch.empty(sum(step) + 64, dtype=dtype, device=dev)
-        out, off = [], 0
-        for sh, n, st in zip(shapes, sizes, step):
-            out.append(buf[off:off + n].view(*sh))
-            off += st
-        return out
+    # The k shard buffers of a tensor stand for memory on k different devices; here they are k allocations
+    # (--layout separate, the default), or k pieces of one allocation back to back (contiguous) or with
+    # --stagger bytes between them (staggered).
+    arena = make_arena(torch, np, args)
 
     t0 = time.time()
     x_full = bf16_dev(cfg["X"])
@@ -172,6 +163,27 @@ def main():
     ms_per_step = wall_ms / args.steps
     k_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i in range(3)]
 
+    # the boxing alone on each of the three buffer layouts (outside the timed region): fresh buffers, the
+    # partials copied from the step's, 10 calls each
+    box_layouts = {}
+    for layout in ("separate", "contiguous", "staggered"):
+        ar = make_arena(torch, np, args, layout)
+        yi, yo = ar([(T, D)] * k, torch.float32), ar([(T, D)] * k, torch.float32)
+        for a, b in zip(yi, y_sh):
+            a.copy_(b)
+        Yi, Yo = sbp.SbpTensor(yi, T, D, sbp.F32), sbp.SbpTensor(yo, T, D, sbp.F32)
+        for _ in range(3):
+            sbp.sbp_boxing(Yi, sbp.P_SUM, Yo, sbp.B, k, stream)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+        e[0].record(stream)
+        for i in range(10):
+            sbp.sbp_boxing(Yi, sbp.P_SUM, Yo, sbp.B, k, stream)
+            e[i + 1].record(stream)
+        torch.cuda.synchronize()
+        box_layouts[layout] = 2.0 * k * T * D * 4 / (e[0].elapsed_time(e[10]) / 10 * 1e-3) / 1e9
+        del yi, yo, Yi, Yo
+    torch.cuda.empty_cache()
+
     flops_gemm = 2.0 * T * D * F                      # per GEMM, summed over the 8 shards
     bytes_box = 2.0 * k * T * D * 4                   # P->B: read k partials, write k copies
     gemm1_tf = flops_gemm / (k_ms[0] * 1e-3) / 1e12
@@ -197,21 +209,26 @@ def main():
         "data": "synthetic",
         "config": {"workload": "Megatron-style MLP block, k=8: X[8192,4096] bf16 B; W1[4096,16384] S(1) -> H S(1) "
                                "(GeLU); W2[16384,4096] S(0) -> Y P(sum); boxing P->B of 8 fp32 8192x4096 partials",
-                   "k": k, "gemm_variant": args.variant},
+                   "k": k, "gemm_variant": args.variant, "shard_buffer_layout": args.layout},
         "kernels": {
             "gemm1_gelu_ms": round(k_ms[0], 4), "gemm1_tflops": round(gemm1_tf, 2),
             "gemm2_psum_ms": round(k_ms[1], 4), "gemm2_tflops": round(gemm2_tf, 2),
             "boxing_p2b_ms": round(k_ms[2], 4), "boxing_gbps": round(box_gbps, 1),
             "matmul_pct_mfma_peak": round(100 * 2 * flops_gemm / ((k_ms[0] + k_ms[1]) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
             "boxing_pct_hbm_peak": round(100 * box_gbps / PEAK_HBM_GBPS, 2),
+            "boxing_gbps_separate": round(box_layouts["separate"], 1),
+            "boxing_gbps_contiguous": round(box_layouts["contiguous"], 1),
+            "boxing_gbps_staggered": round(box_layouts["staggered"], 1),
             "input_gen_s": round(gen_s, 2),
         },
         "roofline": {"bound": "mfma", "kernel": dom_name, "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4),
-                     "traffic": TRAFFIC_BYTES["gemm1" if dom == 0 else "gemm2"], "traffic_unit": "bytes per launch"},
+                     "traffic": TRAFFIC_BYTES["gemm1" if dom == 0 else "gemm2"], "traffic_unit": "bytes per launch",
+                     "traffic_source": TRAFFIC_SOURCE},
         "roofline_boxing": {"bound": "hbm", "kernel": "sbp_boxing P(sum)->B", "achieved": round(box_gbps, 1),
                             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(box_gbps / PEAK_HBM_GBPS, 4),
-                            "traffic": TRAFFIC_BYTES["boxing_p2b"], "traffic_unit": "bytes per launch"},
+                            "traffic": TRAFFIC_BYTES["boxing_p2b"], "traffic_unit": "bytes per launch",
+                            "traffic_source": TRAFFIC_SOURCE},
     }
 
     if not args.no_cpu_baseline:
@@ -222,12 +239,20 @@ def main():
 # ------------------------------------------------------------------------------------------------
 # The other full-size workloads
 # ------------------------------------------------------------------------------------------------
-def make_arena(torch, np, stagger):
-    """k shard buffers carved from one allocation with `stagger` bytes between them (see main)."""
+def make_arena(torch, np, args, layout=None):
+    """arena(shapes, dtype) -> one buffer per shape: separate allocations, or pieces of one allocation back to
+    back (contiguous) or --stagger bytes apart (staggered).  Equal offsets in equally sized back-to-back
+    buffers fall on the same memory channel, which k real devices would not share; the stagger removes that
+    artefact of holding k devices' shards in one HBM."""
+    layout = layout or args.layout
+    gap = {"separate": None, "contiguous": 0, "staggered": args.stagger}[layout]
+
     def arena(shapes, dtype):
+        if gap is None:
+            return [torch.empty(*sh, dtype=dtype, device="cuda") for sh in shapes]
         esz = torch.empty((), dtype=dtype).element_size()
         sizes = [int(np.prod(sh)) for sh in shapes]
-        step = [((n * esz + stagger + 255) // 256 * 256) // esz for n in sizes]
+        step = [((n * esz + gap + 255) // 256 * 256) // esz for n in sizes]
         buf = torch.empty(sum(step) + 64, dtype=dtype, device="cuda")
         out, off = [], 0
         for sh, n, st in zip(shapes, sizes, step):
@@ -271,7 +296,7 @@ def bench_dp_grad(args, cfg, sbp, wl, torch, np):
     k = cfg["k"]
     Tk, Din = cfg["X"]["shape"]
     Dout = cfg["dY"]["shape"][1]
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
     seed = wl.SEED_BASE
     sets = []
     for r in range(3):
@@ -317,7 +342,7 @@ def bench_classifier(args, cfg, sbp, wl, torch, np):
     R, Dm = cfg["F"]["shape"]
     C = cfg["W"]["shape"][1]
     Ci = C // k
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
     seed = wl.SEED_BASE
 
     def bits(spec, rows=None, cols=None):
@@ -381,7 +406,7 @@ def bench_relayout(args, cfg, sbp, wl, torch, np):
     k = cfg["k"]
     R, C = cfg["T"]["shape"]
     Rk, Ck = R // k, C // k
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
     s0 = arena([(Rk, C)] * k, torch.int16)
     for i in range(k):
         s0[i].copy_(torch.from_numpy(wl.pattern_u16((R, C), rows=np.arange(i * Rk, (i + 1) * Rk)).view(np.int16)))
@@ -414,7 +439,7 @@ def bench_uvw(args, cfg, sbp, wl, torch, np):
     (UV), then the row-6 product.  Same matmul work either way; the boxed tensor is [M,N1] or [M,N2]."""
     k = 8
     M, K1, N1, N2 = 4096, 16384, 4096, 1024
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
     seed = wl.SEED_BASE
 
     def bits(tid, shape, std, rows=None, cols=None):
@@ -465,7 +490,7 @@ def bench_zero(args, cfg, sbp, wl, torch, np):
     S(0) (cast fused into the reduce-scatter)."""
     k = 8
     R, C = 16384, 16384
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
     w32 = arena([(R // k, C)] * k, torch.float32)
     for i in range(k):
         rows = np.arange(*shard_range(R, k, i))
@@ -501,7 +526,7 @@ def bench_across(args, cfg, sbp, wl, torch, np):
     [8192,4096] fp32: P(sum) on 8 -> B on 4, P(sum) on 8 -> S(0) on 4."""
     ki, ko = 8, 4
     R, C = 16384, 16384
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
     a8 = arena([(R // ki, C)] * ki, torch.int16)
     for i in range(ki):
         a8[i].copy_(torch.from_numpy(wl.pattern_u16((R, C), rows=np.arange(i * (R // ki), (i + 1) * (R // ki))).view(np.int16)))
@@ -538,16 +563,131 @@ def bench_across(args, cfg, sbp, wl, torch, np):
                        ki, sum(by) / (wall * 1e-3) / 1e9, "GB/s", wall, kernels, roof)
 
 
+class ClockSampler:
+    """Samples the shader clock with `rocm-smi --showclocks` on a thread while a sustained GPU loop runs."""
+
+    def __init__(self):
+        import threading
+        self.clocks, self._stop = [], threading.Event()
+        self._th = threading.Thread(target=self._run)
+
+    def _run(self):
+        import subprocess
+        while not self._stop.is_set():
+            try:
+                txt = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+                for ln in txt.splitlines():
+                    if "sclk" in ln and "Mhz" in ln:
+                        self.clocks.append(int(ln.split("(")[1].split("Mhz")[0]))
+            except Exception:
+                pass
+            self._stop.wait(0.3)
+
+    def __enter__(self):
+        self._th.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._th.join()
+
+    def median(self):
+        c = sorted(self.clocks[1:]) if len(self.clocks) > 2 else sorted(self.clocks)
+        return c[len(c) // 2] if c else None
+
+
+def sustained(torch, call, seconds, batch):
+    """Runs call() back to back for about `seconds`, the shader clock sampled beside it.
+    Returns (ms per call, calls, median sclk MHz)."""
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with ClockSampler() as cs:
+        t0, n = time.perf_counter(), 0
+        e0.record()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(batch):
+                call()
+            n += batch
+            torch.cuda.synchronize()
+        e1.record()
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n, n, cs.median()
+
+
+def bench_mfma_probe(args, cfg, sbp, wl, torch, np):
+    """Diagnostic, not a workload of the paper: what the matrix pipes sustain on this chip with the GEMM kernels'
+    instruction (v_mfma_f32_16x16x32_bf16, 8 waves per compute unit), alone (mode 0), with the operand fragment
+    reads of the lockstep GEMM schedule (mode 1) and of the ping-pong schedule (mode 2), each with pseudo-random
+    and with all-zero operands, run for about 1.5 seconds each with the shader clock sampled.  The kernels
+    count shader cycles themselves: cycles per round of 32 matrix instructions per wave (two waves share a
+    SIMD, so 64 instructions of 16 cycles = 1024 cycles is the floor), and cycles / time = the clock that was
+    actually granted."""
+    iters = 2000
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    scratch = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    flop = cus * 8.0 * iters * 32 * (2 * 16 * 16 * 32)
+    kernels, best = {}, 0.0
+    for mode, name in ((0, "mfma_only"), (3, "mfma_only_32x32x16"), (1, "lockstep_reads"), (2, "pingpong_reads"), (4, "pingpong_12_reads"), (5, "pingpong_8_reads")):
+        for zero, zname in ((0, "random"), (1, "zeros")):
+            ms, n, sclk = sustained(torch, lambda: sbp.sbp_probe_mfma(mode, iters, zero, scratch), 1.5, 100)
+            cyc = scratch[:64].cpu().view(torch.int64).numpy()
+            per_round = float(cyc.max()) / iters
+            tf = flop / ms / 1e9
+            kernels[f"{name}_{zname}"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "cycles_per_round": round(per_round, 1),
+                                          "granted_clock_mhz": round(float(cyc.max()) / ms / 1e3, 0), "sclk_mhz_smi": sclk, "calls": n}
+            if zero == 0:
+                best = max(best, tf)
+    roof = {"bound": "mfma", "kernel": "probe_mfma_kernel, pseudo-random operands, best of the three schedules", "achieved": round(best, 1),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(best / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "diagnostic: v_mfma_f32_16x16x32_bf16 alone / with lockstep fragment reads / in ping-pong, 8 waves per CU, "
+                             "random and zero operands, sustained 1.5 s each", 1, best, "TFLOP/s", kernels["mfma_only_random"]["ms"], kernels, roof)
+
+
+def bench_vendor_gemm(args, cfg, sbp, wl, torch, np):
+    """Diagnostic, not part of the path: the vendor GEMM library (through torch.bmm / torch.matmul, bf16 in, bf16 out)
+    on the three GEMM shapes of the workloads and on the unsharded logical products, N(0, 0.02) operands, sustained
+    two seconds each with the shader clock sampled.  Context for the hand-written kernels' rate on the same chip;
+    its outputs are bf16 where the path writes fp32 partials, so it moves fewer bytes than the path does."""
+    g = torch.Generator(device="cuda").manual_seed(1234)
+
+    def rnd(*shape):
+        return (torch.randn(*shape, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+
+    cases = []
+    x, w1 = rnd(8192, 4096), rnd(8, 4096, 2048)
+    cases.append(("mlp_gemm1_8x[8192,4096]x[4096,2048]", lambda: torch.matmul(x, w1), 2.0 * 8 * 8192 * 4096 * 2048))
+    h, w2 = rnd(8, 8192, 2048), rnd(8, 2048, 4096)
+    cases.append(("mlp_gemm2_8x[8192,2048]x[2048,4096]", lambda: torch.bmm(h, w2), 2.0 * 8 * 8192 * 2048 * 4096))
+    W1f, W2f, hf = rnd(4096, 16384), rnd(16384, 4096), rnd(8192, 16384)
+    cases.append(("mlp_gemm1_unsharded_[8192,4096]x[4096,16384]", lambda: torch.matmul(x, W1f), 2.0 * 8192 * 4096 * 16384))
+    cases.append(("mlp_gemm2_unsharded_[8192,16384]x[16384,4096]", lambda: torch.matmul(hf, W2f), 2.0 * 8192 * 16384 * 4096))
+    xs, dy = rnd(8, 2048, 1024), rnd(8, 2048, 4096)
+    cases.append(("dp_grad_tn_8x[2048,1024]^T x[2048,4096]", lambda: torch.bmm(xs.transpose(1, 2), dy), 2.0 * 8 * 2048 * 1024 * 4096))
+    f, wc = rnd(1024, 512), rnd(8, 512, 125000)
+    cases.append(("classifier_8x[1024,512]x[512,125000]", lambda: torch.matmul(f, wc), 2.0 * 8 * 1024 * 512 * 125000))
+    kernels, best = {}, 0.0
+    for name, call, flop in cases:
+        ms, n, sclk = sustained(torch, call, 2.0, 50)
+        tf = flop / ms / 1e9
+        kernels[name] = {"ms": round(ms, 4), "tflops": round(tf, 1), "sclk_mhz_smi": sclk, "calls": n}
+        best = max(best, tf)
+    roof = {"bound": "mfma", "kernel": "vendor library GEMM through torch (bf16 out), best shape", "achieved": round(best, 1),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(best / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "diagnostic: vendor-library bf16 GEMM (torch.matmul / torch.bmm) on the workloads' GEMM shapes, sustained 2 s each",
+                       8, best, "TFLOP/s", kernels[cases[0][0]]["ms"], kernels, roof)
+
+
 def bench_clock_probe(args, cfg, sbp, wl, torch, np):
     """Diagnostic, not a workload of the paper: GEMM2 of the MLP block, (S1,S0)->P(sum), run back to back for
-    a few seconds with N(0, 0.02) operands and again with all-zero operands, while `rocm-smi --showclocks`
-    samples the shader clock.  Same kernel, same launches: the difference is what the chip's power
-    management does with the operand data."""
-    import subprocess
-    import threading
+    three seconds with N(0, 0.02) operands and again with all-zero operands, with the lockstep kernel (the
+    default for this shape) and with the ping-pong kernel (variant 21), while `rocm-smi --showclocks` samples
+    the shader clock.  Same kernels, same launches: the difference between the operand sets is what the chip's
+    power management does with the operand data."""
     k, M, N, K = 8, 8192, 4096, 16384
-    arena = make_arena(torch, np, args.stagger)
-    out = {}
+    arena = make_arena(torch, np, args)
+    kernels, res = {}, {}
     for mode in ("normal", "zero"):
         xs = arena([(M, K // k)] * k, torch.bfloat16)
         ws = arena([(K // k, N)] * k, torch.bfloat16)
@@ -555,49 +695,22 @@ def bench_clock_probe(args, cfg, sbp, wl, torch, np):
         for t in xs + ws:
             t.zero_() if mode == "zero" else t.normal_(0.0, 0.02)
         X, W, Y = sbp.SbpTensor(xs, M, K, sbp.BF16), sbp.SbpTensor(ws, K, N, sbp.BF16), sbp.SbpTensor(ys, M, N, sbp.F32)
-        clocks, stop = [], threading.Event()
-
-        def sampler():
-            while not stop.is_set():
-                try:
-                    txt = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
-                    for ln in txt.splitlines():
-                        if "sclk" in ln and "Mhz" in ln:
-                            clocks.append(int(ln.split("(")[1].split("Mhz")[0]))
-                except Exception:
-                    pass
-                stop.wait(0.3)
-
-        for _ in range(5):
-            sbp.sbp_matmul(X, sbp.S(1), W, sbp.S(0), Y, sbp.P_SUM, k)
-        torch.cuda.synchronize()
-        th = threading.Thread(target=sampler)
-        th.start()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0, n = time.perf_counter(), 0
-        e0.record()
-        while time.perf_counter() - t0 < 3.0:
-            for _ in range(50):
-                sbp.sbp_matmul(X, sbp.S(1), W, sbp.S(0), Y, sbp.P_SUM, k)
-            n += 50
-            torch.cuda.synchronize()
-        e1.record()
-        torch.cuda.synchronize()
-        stop.set()
-        th.join()
-        ms = e0.elapsed_time(e1) / n
-        steady = sorted(clocks[1:]) if len(clocks) > 2 else sorted(clocks)
-        out[mode] = (ms, 2.0 * M * N * K / ms / 1e9, steady[len(steady) // 2] if steady else None, n)
+        for variant, vname in ((args.variant, "gemm2"), (21, "gemm2_pingpong")):
+            sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, variant)
+            ms, n, sclk = sustained(torch, lambda: sbp.sbp_matmul(X, sbp.S(1), W, sbp.S(0), Y, sbp.P_SUM, k), 3.0, 50)
+            res[(vname, mode)] = (ms, 2.0 * M * N * K / ms / 1e9)
+            kernels[f"{vname}_{mode}_ms"] = round(ms, 4)
+            kernels[f"{vname}_{mode}_tflops"] = round(res[(vname, mode)][1], 1)
+            kernels[f"{vname}_{mode}_sclk_mhz"] = sclk
+            kernels[f"{vname}_{mode}_calls"] = n
+        sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, args.variant)
         del xs, ws, ys, X, W, Y
         torch.cuda.empty_cache()
-    kernels = {"gemm2_normal_ms": round(out["normal"][0], 4), "gemm2_normal_tflops": round(out["normal"][1], 1),
-               "sclk_mhz_normal": out["normal"][2], "gemm2_zero_ms": round(out["zero"][0], 4),
-               "gemm2_zero_tflops": round(out["zero"][1], 1), "sclk_mhz_zero": out["zero"][2],
-               "calls_each": [out["normal"][3], out["zero"][3]]}
-    roof = {"bound": "mfma", "kernel": "sbp_matmul (S1,S0)->P(sum), N(0,0.02) operands, sustained", "achieved": round(out["normal"][1], 1),
-            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(out["normal"][1] / PEAK_BF16_TFLOPS, 4), "traffic": None}
-    return result_line(args, "diagnostic: sustained GEMM2 of the MLP block with N(0,0.02) and with all-zero operands, shader clock sampled",
-                       k, out["normal"][1], "TFLOP/s", out["normal"][0], kernels, roof)
+    ms, tf = res[("gemm2", "normal")]
+    roof = {"bound": "mfma", "kernel": "sbp_matmul (S1,S0)->P(sum), N(0,0.02) operands, sustained", "achieved": round(tf, 1),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    return result_line(args, "diagnostic: sustained GEMM2 of the MLP block with N(0,0.02) and with all-zero operands, lockstep and ping-pong kernels, "
+                             "shader clock sampled", k, tf, "TFLOP/s", ms, kernels, roof)
 
 
 def bench_tiny(args, cfg, sbp, wl, torch, np):
@@ -640,7 +753,7 @@ def bench_grid(args, cfg, sbp, wl, torch, np):
     k0, k1 = 2, 4
     k = k0 * k1
     S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
-    arena = make_arena(torch, np, args.stagger)
+    arena = make_arena(torch, np, args)
 
     def fill(ts, std):
         for t in ts:
@@ -678,7 +791,7 @@ def bench_grid(args, cfg, sbp, wl, torch, np):
                        k, 2 * flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
 
 
-OTHER_WORKLOADS = {"grid": bench_grid, "tiny": bench_tiny, "clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
+OTHER_WORKLOADS = {"mfma_probe": bench_mfma_probe, "vendor_gemm": bench_vendor_gemm, "grid": bench_grid, "tiny": bench_tiny, "clock_probe": bench_clock_probe, "across": bench_across, "dp_grad": bench_dp_grad, "classifier": bench_classifier, "relayout": bench_relayout, "uvw": bench_uvw,
                    "zero": bench_zero}
 
 

@@ -268,7 +268,8 @@ int32_t sbp_set_knob(int32_t knob, int32_t value);
  * every wave runs `iters` rounds of 32 v_mfma_f32_16x16x32_bf16 (2 * 16 * 16 * 32 flop each per wave).
  *   mode 0: matrix instructions only; 1: with 16 LDS fragment reads per round interleaved in both waves of a
  *   SIMD and a barrier per round (lockstep schedule); 2: the two waves of a SIMD alternating between their
- *   reads and their matrix instructions (ping-pong schedule).
+ *   reads and their matrix instructions (ping-pong schedule); 3: as 0 with 16 v_mfma_f32_32x32x16_bf16 per
+ *   round (same flop); 4, 5: as 2 with 12 and with 8 fragment reads per round.
  *   zero_operands != 0: all-zero fragments instead of pseudo-random ones (no operand toggling).
  *   scratch: 1 MiB of device memory, 16-byte aligned, caller-owned; after the call has completed its first
  *   8 uint64 words hold the shader cycles each wave of workgroup 0 spent in the loop.

@@ -1264,20 +1264,26 @@ __device__ inline SplitTerms split_f32x8(const f32x4 a, const f32x4 b) {
     return t;
 }
 
-template <bool A_KC, bool B_KC, bool F32_B>
-__global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int tn, int order) {
-    constexpr int BM = 128, BN = 128, WN = 2, NT = 256, BKT = 32;
+// HW: extent of the bf16 operand's side of the tile, 128 (4 waves) or 256 (8 waves).  The split costs about as many
+// vector instructions per element of the fp32 operand as fit beside the matrix instructions of a 128-wide tile;
+// with 256 every split element feeds twice as many of them and the bf16 operand is fetched half as often.
+template <bool A_KC, bool B_KC, bool F32_B, int HW>
+__global__ __launch_bounds__(HW * 2, HW == 256 ? 4 : 2) void gemm_split_kernel(GemmPlan p, int tm, int tn, int order) {
+    constexpr int BM = F32_B ? HW : 128, BN = F32_B ? 128 : HW, WN = BN / 64, NT = HW * 2, BKT = 32;
     constexpr int TM = 64, TN = 64, FM = 4, FN = 4;   // 16 x 16 blocks of v_mfma_f32_16x16x32_bf16 (one per 32-deep stage)
     using TA = Tile<BM, A_KC, NT, BKT, true>;
     using TB = Tile<BN, B_KC, NT, BKT, true>;
     using TF = std::conditional_t<F32_B, TB, TA>;   // tile type of the fp32 operand
     using TH = std::conditional_t<F32_B, TA, TB>;   // ... of the bf16 operand
-    static_assert(TA::BYTES == TB::BYTES, "square tile");
-    __shared__ __attribute__((aligned(1024))) char sF0[3][TF::BYTES];   // hi, mid, lo
-    __shared__ __attribute__((aligned(1024))) char sF1[3][TF::BYTES];
+    // two stages of three term tiles (hi, mid, lo); after the reduction loop the same memory serves as the
+    // epilogue's per-wave windows, so that two workgroups fit a compute unit's LDS with either tile
+    __shared__ __attribute__((aligned(1024))) char sFF[2][3][TF::BYTES];
     __shared__ __attribute__((aligned(1024))) char sH0[TH::BYTES];
     __shared__ __attribute__((aligned(1024))) char sH1[TH::BYTES];
-    __shared__ __attribute__((aligned(1024))) char sOut[4 * STAGE_BYTES];
+    static_assert(sizeof(sFF) >= (NT / 64) * STAGE_BYTES, "epilogue windows fit the term tiles");
+    char (*sF0)[TF::BYTES] = sFF[0];
+    char (*sF1)[TF::BYTES] = sFF[1];
+    char* sOut = &sFF[0][0][0];
 
     const TileCoord tc = map_tile(blockIdx.x, gridDim.x, tm, tn, p.groups, order);
     if (!tc.valid) return;
@@ -1386,21 +1392,33 @@ __global__ __launch_bounds__(256) void gemm_split_kernel(GemmPlan p, int tm, int
         step(I1{}, t + 2 < steps);
     }
     if (steps & 1) step(I0{}, false);
+    // every step ends with a workgroup barrier: nobody reads the term tiles any more
     store_tile16<BM, BN, TM, TN, SBP_EPI_NONE, float>(acc, s, m0, n0, wm, wn, lane, sOut);
 }
 
-template <bool F32_B>
-int32_t launch_split(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
-    const int tm = (max_m + 127) / 128, tn = (max_n + 127) / 128;
+template <bool F32_B, int HW>
+int32_t launch_split_cfg(const GemmPlan& plan, int max_m, int max_n, hipStream_t st) {
+    constexpr int BM = F32_B ? HW : 128, BN = F32_B ? 128 : HW;
+    const int tm = (max_m + BM - 1) / BM, tn = (max_n + BN - 1) / BN;
     const int64_t nblk = ((int64_t)tm * tn * plan.groups + 7) / 8 * 8;
     if (nblk > 0x7FFFFFFF) return SBP_ERR_UNSUPPORTED;
     void (*kern)(GemmPlan, int, int, int);
-    if (plan.a_kc && plan.b_kc) kern = gemm_split_kernel<true, true, F32_B>;
-    else if (plan.a_kc) kern = gemm_split_kernel<true, false, F32_B>;
-    else if (plan.b_kc) kern = gemm_split_kernel<false, true, F32_B>;
-    else kern = gemm_split_kernel<false, false, F32_B>;
-    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(256), 0, st, plan, tm, tn, tile_order_for(tm, tn));
+    if (plan.a_kc && plan.b_kc) kern = gemm_split_kernel<true, true, F32_B, HW>;
+    else if (plan.a_kc) kern = gemm_split_kernel<true, false, F32_B, HW>;
+    else if (plan.b_kc) kern = gemm_split_kernel<false, true, F32_B, HW>;
+    else kern = gemm_split_kernel<false, false, F32_B, HW>;
+    hipLaunchKernelGGL(kern, dim3((uint32_t)nblk), dim3(HW * 2), 0, st, plan, tm, tn, tile_order_for(tm, tn));
     return launch_status(__func__);
+}
+
+// The wide tile when the bf16 operand's side has at least 256 rows or columns and the narrow tiling would
+// still leave every compute unit several workgroups; `variant` 31 / 32 force the narrow / the wide tile.
+template <bool F32_B>
+int32_t launch_split(const GemmPlan& plan, int max_m, int max_n, int variant, hipStream_t st) {
+    const int hside = F32_B ? max_m : max_n;
+    const int64_t wide_tiles = (int64_t)((max_m + (F32_B ? 255 : 127)) / (F32_B ? 256 : 128)) * ((max_n + (F32_B ? 127 : 255)) / (F32_B ? 128 : 256)) * plan.groups;
+    const bool wide = variant == 32 || (variant != 31 && hside >= 256 && wide_tiles >= 2 * (int64_t)compute_units());
+    return wide ? launch_split_cfg<F32_B, 256>(plan, max_m, max_n, st) : launch_split_cfg<F32_B, 128>(plan, max_m, max_n, st);
 }
 
 template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC, int ODD, int EPI, typename OutT>
@@ -1531,12 +1549,14 @@ int32_t launch_gemm(const GemmPlan& plan, int32_t variant, hipStream_t stream) {
     if (plan.epilogue == EPI_ROWMAX && (max_m == 0 || max_n == 0 || plan.f32_operand || variant == 1 || !mfma_ok(plan)))
         return SBP_ERR_UNSUPPORTED;
     if (max_m == 0 || max_n == 0) return SBP_OK;   // every local product is empty
+    // variants 31 / 32 choose the tile of the split kernel only; every other product takes the default path
+    if ((variant == 31 || variant == 32) && !(plan.f32_operand && split_ok(plan))) variant = 0;
 
     if (plan.f32_operand) {
         // Table 1 rows 4 / 5 with a bf16 partner: split kernel, else the generic kernel with mixed element types
         if (variant != 1 && split_ok(plan)) {
-            if (variant > 1) return SBP_ERR_UNSUPPORTED;
-            return plan.f32_operand == 2 ? launch_split<true>(plan, max_m, max_n, stream) : launch_split<false>(plan, max_m, max_n, stream);
+            if (variant > 1 && variant != 31 && variant != 32) return SBP_ERR_UNSUPPORTED;
+            return plan.f32_operand == 2 ? launch_split<true>(plan, max_m, max_n, variant, stream) : launch_split<false>(plan, max_m, max_n, variant, stream);
         }
         if (variant > 1) return SBP_ERR_UNSUPPORTED;
         const dim3 grid((max_n + 15) / 16, (max_m + 15) / 16, plan.groups);

@@ -11,6 +11,8 @@
 //   mode 2  ping-pong: the waves 4-7 run one phase behind the waves 0-3; a wave alternates between reading its
 //           16 fragments and issuing its 32 matrix instructions, a barrier between phases
 //                                                              (the schedule of gemm_pingpong_kernel)
+//   mode 3  as mode 0 with v_mfma_f32_32x32x16_bf16 (16 instructions of twice the work per round)
+//   mode 4, 5  as mode 2 with 12 and with 8 fragment reads per round: what the fragment traffic costs
 // zero != 0 fills the fragments with zeros instead of pseudo-random bf16 values of magnitude 1: same instructions,
 // no operand toggling; the chip's power management then grants a higher clock.
 #include "sbp_internal.h"
@@ -24,7 +26,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int PROBE_SLOTS = 6144;   // 16-byte fragments per lane-row in LDS: 96 KB
 
-template <int MODE>
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <int MODE, int NRD = 16>
 __global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cycles, float* sink, int iters, int zero) {
     __shared__ bf16x8 lds[PROBE_SLOTS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -55,7 +59,14 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cyc
     if (MODE == 2 && wave >= 4) __builtin_amdgcn_s_barrier();   // the second group runs one phase behind
     const unsigned long long t0 = __builtin_readcyclecounter();
     for (int it = 0; it < iters; ++it) {
-        if constexpr (MODE == 0) {
+        if constexpr (MODE == 3) {
+            // the 16 accumulator blocks of 16x16 regrouped as 4 blocks of 32x32
+            f32x16* big = reinterpret_cast<f32x16*>(acc);
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) big[q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[g][q & 3], fa[g][q >> 1], big[q & 3], 0, 0, 0);
+        } else if constexpr (MODE == 0) {
 #pragma unroll
             for (int g = 0; g < 2; ++g)
 #pragma unroll
@@ -79,8 +90,8 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cyc
             for (int s = 0; s < 2; ++s)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    fa[s][i] = lds[lane + 64 * ((i + it + 16 * s) & 63)];
-                    fb[s][i] = lds[lane + 64 * ((i + it + 7 + 16 * s) & 63)];
+                    if (8 * s + i < NRD) fa[s][i] = lds[lane + 64 * ((i + it + 16 * s) & 63)];
+                    if (8 * s + 4 + i < NRD) fb[s][i] = lds[lane + 64 * ((i + it + 7 + 16 * s) & 63)];
                 }
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
             __builtin_amdgcn_sched_barrier(0);
@@ -113,7 +124,10 @@ int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scrat
     float* sink = reinterpret_cast<float*>(static_cast<char*>(scratch) + 64);
     if (mode == 0) hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
     else if (mode == 1) hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
-    else hipLaunchKernelGGL(probe_mfma_kernel<2>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
+    else if (mode == 2) hipLaunchKernelGGL(probe_mfma_kernel<2>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
+    else if (mode == 3) hipLaunchKernelGGL(probe_mfma_kernel<3>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
+    else if (mode == 4) hipLaunchKernelGGL((probe_mfma_kernel<2, 12>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
+    else hipLaunchKernelGGL((probe_mfma_kernel<2, 8>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
     return launch_status(__func__);
 }
 

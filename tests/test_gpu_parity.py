@@ -299,12 +299,14 @@ def test_matmul_bf16_persistent_kernel(sx, sw, tx, tw, kshard, variant):
 
 @pytest.mark.parametrize("tx,tw", [(0, 0), (1, 0), (0, 1), (1, 1)])
 @pytest.mark.parametrize("row", [4, 5])
-@pytest.mark.parametrize("shape", [(296, 192, 328), (45, 100, 51)])
-def test_matmul_partial_fp32_times_bf16(row, tx, tw, shape):
+@pytest.mark.parametrize("shape,variant", [((296, 192, 328), 0), ((296, 192, 328), 32), ((600, 96, 536), 32), ((45, 100, 51), 0)])
+def test_matmul_partial_fp32_times_bf16(row, tx, tw, shape, variant):
     """Table 1 rows 4 and 5 inside a bf16 graph: the P(sum) operand is k fp32 partials, its partner a
     bf16 B tensor, the result k fp32 partials Y_i = X_i W (or X W_i).  The first shape takes the
-    MFMA kernel that splits the fp32 operand into three bf16 terms (several tiles, ragged edges),
-    the second the generic kernel.  Both keep fp32-GEMM accuracy: the partial is never rounded."""
+    MFMA kernel that splits the fp32 operand into three bf16 terms (several tiles, ragged edges), with
+    its 128 x 128 tile (the choice for small shapes) and with the 128 x 256 tile forced (variant 32), which
+    the third shape runs over several tiles in both directions and an odd number of reduction steps;
+    the last shape takes the generic kernel.  All keep fp32-GEMM accuracy: the partial is never rounded."""
     k = 3
     M, K, N = shape
     X, W = rnd_f32(1, (M, K)), rnd_f32(2, (K, N))
@@ -321,10 +323,10 @@ def test_matmul_partial_fp32_times_bf16(row, tx, tw, shape):
         sx, sw = orc.B, orc.P_SUM
         ref, sy = orc.matmul_sbp([values(x) for x in Xs], sx, Ws, sw)
     assert sy == orc.P_SUM
-    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx, tw)
+    got, _ = run_matmul(Xs, sx, Ws, sw, M, K, N, k, tx, tw, variant=variant)
     for i in range(k):
         assert got[i].dtype == np.float32 and got[i].shape == ref[i].shape
-        assert_matmul_close(got[i], ref[i], 1e-5, f"row {row} trans=({tx},{tw}) shape={shape} partial {i}")
+        assert_matmul_close(got[i], ref[i], 1e-5, f"row {row} trans=({tx},{tw}) shape={shape} variant={variant} partial {i}")
 
 
 def test_matmul_bf16_persistent_kernel_uneven_shards():
