@@ -723,12 +723,15 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     //                 (box_reduce_diag_kernel): 5.36 / 5.26 / 5.43
     // One vector per lane is the fastest on large tensors unless the k buffers lie back to back (equal offsets then
     // share a memory bank, and the k stores of a lane hit it in a row); four lose 3 % there and hold up on every
-    // layout, so four it is.  Small tensors (up to 32 MiB per source) take the out-of-phase kernel where it exists.
+    // layout, so four it is.  Medium tensors (above 8 and up to 32 MiB per source, all tasks together) take the
+    // out-of-phase kernel where it exists; below that its k vectors per lane leave too few workgroups (8 partials of
+    // 1 / 4 MiB: 13 / 16 us against 7.6 / 11 with four vectors per lane; 16 MiB: 45 against 49).
     int unroll = 1;
     if (reduce && vbytes == 16) {
-        const bool small = max_units <= ((int64_t)1 << 21);
+        const int64_t all_units = max_units * tasks;
+        const bool medium = all_units > ((int64_t)1 << 19) && all_units <= ((int64_t)1 << 21);
         const bool diag = p.mode != M_P2P && (p.ki == 4 || p.ki == 8 || p.ki == 16);
-        unroll = small ? (diag ? 16 : 8) : 4;
+        unroll = medium ? (diag ? 16 : 8) : 4;
         const int forced = g_box_reduce_variant.load(std::memory_order_relaxed);
         if (forced) unroll = (forced == 16 && !diag) ? 8 : forced;
     }
