@@ -271,6 +271,16 @@ __device__ inline float mfma_epilogue(float v) {
     else return v;
 }
 
+// max(a, b, c) in one instruction, a NaN operand ignored next to a number (the hardware's maxNum).  Written as
+// assembly because fmaxf() on values the compiler cannot prove canonical (matrix-instruction results) costs a
+// canonicalising multiply per operand: 300 instead of 64 vector instructions per tile and wave in the fused row
+// maximum.
+__device__ inline float max3f(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 constexpr int STAGE_BYTES = 4096;
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }   // s_waitcnt vmcnt(n), nothing else
 

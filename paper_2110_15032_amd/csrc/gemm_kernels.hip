@@ -82,11 +82,13 @@ std::atomic<int> g_tile_order{0};
 // Band height when the knob leaves it open.  Measured with the persistent kernels, ms at band
 // 1 / 2 / 3 / 4 / 6 / 8 / 16: 32 x 8 tiles per shard (K = 4096) .815 / .809 / .805 / .812 / .828 / .844 / .932;
 // 32 x 16 tiles (K = 2048 per shard) .947 / .945 / .906 / .905 / .897 / .900 / 1.18; 4 x 489 tiles: 3 or 4.
-// So 2 for narrow shards, 6 for wide ones with enough tile-rows to fill whole bands, else 3.
+// So 2 for narrow shards, 6 for wide ones with enough tile-rows to fill whole bands, else 3; 4 for four tile-rows: a
+// workgroup of the persistent walk then stays in the same rows from tile to tile (256 is a multiple of the band),
+// which the fused row maximum uses.
 inline int tile_order_for(int tm, int tn) {
     const int knob = g_tile_order.load(std::memory_order_relaxed);
     if (knob & 0xFF) return knob;
-    return (knob & ~0xFF) | (tn <= 8 ? 2 : tm >= 12 ? 6 : 3);
+    return (knob & ~0xFF) | (tn <= 8 ? 2 : tm >= 12 ? 6 : tm == 4 ? 4 : 3);
 }
 
 

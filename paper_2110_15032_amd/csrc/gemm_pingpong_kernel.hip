@@ -29,6 +29,13 @@
 //     A group stores its half of a finished tile at the start of its next load phase, i.e. while the
 //     other group still computes; the two epilogues of a tile do not coincide.
 //
+// (3) The fused row maximum (sbp_matmul_rowmax, Sec. 6.3.1) is carried in registers from tile to tile while the
+//     tile walk stays in the same rows and reaches the P(max) vector only when the rows change (see runpk).
+//
+// Registers: 128 accumulators + 48 fragment registers of 256, and the unrolled four-stage loop needs most of the
+// rest for LDS addresses; whatever is only needed at a tile change (lane id and everything derived from it) is
+// recomputed there.  A spill would be more than a slow access: its reload waits for the whole memory counter.
+//
 // Loads and stores are inline assembly outside the compiler's bookkeeping (see gemm_device.h) and every
 // wait on the memory counter is explicit.  The counter retires in issue order.  Before the barrier that
 // opens load(s + 1) of waves 0-3 (the first reader of stage s + 1) every wave waits for its part of that
@@ -62,12 +69,12 @@ __device__ inline void load16_lds(uint32_t lds_base, gbl_char* src, uint32_t vof
 // the part of an output tile that one wave writes (all uniform)
 struct OutTile {
     char* base;        // element (m0 + wm * 128, n0 + wn * 64)
-    float* rowmax;     // EPI_ROWMAX: entry of row m0 + wm * 128
     uint32_t rowblk;   // bytes between row blocks (16 rows)
     int32_t ldc;
     bool stream;       // row pitch a multiple of 128 bytes: whole lines, stored past the cache
     bool whole;        // not cut by the matrix edge, rows 16-byte aligned
     int32_t rows_left, cols_left;   // of the matrix, from the wave tile's first row / column on
+    int32_t rows_key;               // (shard << 16 | tile row) + 1: names the rows this wave writes
 };
 
 template <bool A_KC, bool B_KC, int EPI, typename OutT>
@@ -78,7 +85,7 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
     using TB = Tile<BN, B_KC, NTL, BKT, true>;
     static_assert(TA::PER_THREAD == TB::PER_THREAD, "both groups issue the same number of loads");
     constexpr int NL = TA::PER_THREAD;                                           // loads per stage and wave (4)
-    constexpr int NSW = (F32OUT ? 32 : 16) + (EPI == EPI_ROWMAX ? 4 : 0);        // stores (+ atomics) per tile and wave
+    constexpr int NSW = F32OUT ? 32 : 16;                                        // stores per tile and wave
     static_assert(2 * NL + NSW < 64, "vmcnt field");
     // four stages in one array (stage b: X tile at b * STAGE, W tile behind it), so that every LDS address a
     // load needs is one scalar base plus an immediate
@@ -90,6 +97,13 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the lane id again, from the hardware and opaque to the compiler: what the epilogue and the tile changes derive
+    // from it is recomputed there instead of occupying a register all through the reduction loop, which has none to spare
+    auto lane_again = []() {
+        int l;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+        return l;
+    };
     const int grp = wave >> 2;            // 0: loads operands and runs one phase ahead; 1: one phase behind
     const int wm = grp, wn = wave & 3;
     const int G = gridDim.x;
@@ -108,19 +122,21 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
     // ---- load cursor (waves 0-3): stage after stage, tile after tile, three steps ahead of compute ----
     gbl_char* A = nullptr;
     gbl_char* B = nullptr;
-    uint32_t offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+    uint32_t off[NL];          // per-lane source offsets of this wave's loads: of the X tile in waves 0-3, of the W tile in waves 4-7
     uint32_t stepa = 0, stepb = 0;
     auto open_tile = [&](int v) {
         const TileCoord tc = map_tile(v, nblk, tm, tn, p.groups, order);
         const GemmShard& s = p.s[tc.g];
         A = (gbl_char*)s.a;
         B = (gbl_char*)s.b;
-        int t = tid & (NTL - 1);
-        asm volatile("" : "+v"(t));   // recomputed per tile instead of held in registers
+        const int t = (wave & 3) * 64 + lane_again();   // thread index within the four waves that load this operand
+        if (grp == 0) {
 #pragma unroll
-        for (int it = 0; it < TA::PER_THREAD; ++it) offa[it] = TA::src_offset(s.lda, tc.tile_m * BM, s.m, it * NTL + t);
+            for (int it = 0; it < NL; ++it) off[it] = TA::src_offset(s.lda, tc.tile_m * BM, s.m, it * NTL + t);
+        } else {
 #pragma unroll
-        for (int it = 0; it < TB::PER_THREAD; ++it) offb[it] = TB::src_offset(s.ldb, tc.tile_n * BN, s.n, it * NTL + t);
+            for (int it = 0; it < NL; ++it) off[it] = TB::src_offset(s.ldb, tc.tile_n * BN, s.n, it * NTL + t);
+        }
         stepa = TA::step_bytes(s.lda);
         stepb = TB::step_bytes(s.ldb);
     };
@@ -129,8 +145,8 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
     const uint32_t lds_wave = (uint32_t)(uintptr_t)(lds_void*)smem + (uint32_t)wn * 1024u;   // this wave's 64 chunks of a 256-chunk row of loads
     auto issue = [&](auto dst) {
         constexpr int D = decltype(dst)::value;
-        if (grp == 0) static_for<TA::PER_THREAD>([&](auto it) { load16_lds<D * STAGE + decltype(it)::value * NTL * 16>(lds_wave, A, offa[decltype(it)::value]); });
-        else static_for<TB::PER_THREAD>([&](auto it) { load16_lds<D * STAGE + TA::BYTES + decltype(it)::value * NTL * 16>(lds_wave, B, offb[decltype(it)::value]); });
+        if (grp == 0) static_for<NL>([&](auto it) { load16_lds<D * STAGE + decltype(it)::value * NTL * 16>(lds_wave, A, off[decltype(it)::value]); });
+        else static_for<NL>([&](auto it) { load16_lds<D * STAGE + TA::BYTES + decltype(it)::value * NTL * 16>(lds_wave, B, off[decltype(it)::value]); });
         A += stepa;
         B += stepb;
     };
@@ -152,10 +168,64 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
     //   bf16 (8 chunks per row, two rows span the banks): chunk ^ ((row >> 1) & 7).  A write pass (8 bytes per lane):
     //        the eight even rows take eight different chunks in one half of the banks, the odd rows in the other;
     //        a read pass: two neighbouring rows, same permutation, different halves.
+    // EPI_ROWMAX (Sec. 6.3.1, local row maximum): lane (g, c) keeps, for each of its 8 row blocks i, the maximum of the
+    // values it has stored of row 16 i + c (its columns 16 j + 4 g + 0..3 of every tile), carried from tile to tile while
+    // the tile walk stays in the same rows: one max3 per two values per tile, plus unpacking and repacking the eight
+    // running values, which are kept as bf16 pairs in four registers (eight would not stay in registers across the
+    // reduction loop, and a spill brings the compiler's own full wait on the memory counter into every tile).  Only when the rows change
+    // or the kernel ends do the four lanes of a row combine (two lane swaps) and one pair of atomics per 64 rows fold
+    // the result into the P(max) vector: a shard's column tiles would otherwise all send atomics to the same few cache
+    // lines.  The maximum is taken over the fp32 results and rounded once: rounding to nearest even is monotonic, so
+    // that is the maximum of the stored bf16 values.  The extra memory operations of a flush only make the counted
+    // waits behind it stricter.
+    [[maybe_unused]] uint32_t runpk[4];      // row blocks 2 q (low half) and 2 q + 1 (high half), bf16
+    [[maybe_unused]] int run_key = 0;        // OutTile::rows_key of the rows the running maxima belong to, 0 = none yet (uniform)
+    if constexpr (EPI == EPI_ROWMAX) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) runpk[q] = 0xFF80FF80u;   // -inf, -inf
+    }
+    [[maybe_unused]] auto flush_rowmax = [&]() {
+        const int ln = lane_again();
+        const int g = ln >> 4;
+        const GemmShard& rs = p.s[(run_key - 1) >> 16];
+        const int first_row = ((run_key - 1) & 0xFFFF) * BM + wm * TM;
+        float* run_ptr = rs.rowmax + first_row;
+        const int run_rows = rs.m - first_row;      // 128 or more: all of the wave's rows exist
+        float r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t x = (i & 1) ? (runpk[i >> 1] & 0xFFFF0000u) : (runpk[i >> 1] << 16);
+            const auto a = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+            const uint32_t m = __float_as_uint(max3f(__uint_as_float(a[0]), __uint_as_float(a[1]), __uint_as_float(a[1])));
+            const auto b = __builtin_amdgcn_permlane16_swap(m, m, false, false);
+            r[i] = max3f(__uint_as_float(b[0]), __uint_as_float(b[1]), __uint_as_float(b[1]));
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) runpk[q] = 0xFF80FF80u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // lane 16 g + c carries row 64 h + 16 g + c, i.e. row c of row block 4 h + g
+            float vmax = g == 0 ? r[4 * h] : g == 1 ? r[4 * h + 1] : g == 2 ? r[4 * h + 2] : r[4 * h + 3];
+            vmax = bf16_to_f32(f32_to_bf16(vmax)) + 0.0f;
+            float* dst = run_ptr + h * 64 + ln;
+            const bool row_ok = h * 64 + ln < run_rows;
+            // signed max for non-negative values, unsigned min for negative ones (see atomic_max_f32_untracked), each
+            // under its own lanes; a NaN never entered the running maximum
+            const uint64_t mp = __builtin_amdgcn_ballot_w64(row_ok && vmax >= 0.0f), mn = __builtin_amdgcn_ballot_w64(row_ok && vmax < 0.0f);
+            asm volatile("s_mov_b64 exec, %2\n\tglobal_atomic_smax %0, %1, off\n\ts_mov_b64 exec, %3\n\tglobal_atomic_umin %0, %1, off\n\ts_mov_b64 exec, -1"
+                         : : "v"(dst), "v"(vmax), "s"(mp), "s"(mn) : "memory");
+        }
+    };
+
     auto store_tile = [&](const OutTile& ot) {
-        int ln = lane;
-        asm volatile("" : "+v"(ln));
+        const int ln = lane_again();
         const int g = ln >> 4, c = ln & 15;
+        if constexpr (EPI == EPI_ROWMAX) {
+            if (run_key != ot.rows_key) {            // uniform: other rows than the running maxima belong to
+                if (run_key) flush_rowmax();
+                run_key = ot.rows_key;
+            }
+        }
         if (ot.whole) {
             char* win = swin + wave * 4096;
             const int rr = ln >> 3, rk = ln & 7;           // read side: row (of 8), chunk (of 8)
@@ -193,23 +263,25 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
                     rd[tt] = row * 128 + ((rk ^ ((row >> 1) & 7)) << 4);
                 }
                 const uint32_t vofs = (uint32_t)(rr * ot.ldc) * 2u + (uint32_t)rk * 16u;
-                [[maybe_unused]] float rmx[4];
                 static_for<4>([&](auto idx) {
                     constexpr int IP = decltype(idx)::value;      // row blocks 2 IP, 2 IP + 1 share the window
+                    [[maybe_unused]] float pairmx[2];
                     static_for<2>([&](auto sub) {
                         constexpr int IA = 2 * IP + decltype(sub)::value;
-                        [[maybe_unused]] float mx = -__builtin_inff();
+                        [[maybe_unused]] float mx = 0.0f;
+                        if constexpr (EPI == EPI_ROWMAX) mx = __uint_as_float((IA & 1) ? (runpk[IP] & 0xFFFF0000u) : (runpk[IP] << 16));
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const float v0 = mfma_epilogue<EPI>(acc[IA][j][0]), v1 = mfma_epilogue<EPI>(acc[IA][j][1]);
                             const float v2 = mfma_epilogue<EPI>(acc[IA][j][2]), v3 = mfma_epilogue<EPI>(acc[IA][j][3]);
-                            if constexpr (EPI == EPI_ROWMAX) mx = fmaxf(mx, fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)));
+                            if constexpr (EPI == EPI_ROWMAX) mx = max3f(max3f(mx, v0, v1), v2, v3);
                             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                             const u32x2 w = {f32_to_bf16x2(v0, v1), f32_to_bf16x2(v2, v3)};
                             *reinterpret_cast<u32x2*>(win + (decltype(sub)::value * 2048 + (wbase ^ (j << 5)))) = w;
                         }
-                        if constexpr (EPI == EPI_ROWMAX) rmx[IA & 3] = mx;
+                        if constexpr (EPI == EPI_ROWMAX) pairmx[IA & 1] = mx;
                     });
+                    if constexpr (EPI == EPI_ROWMAX) runpk[IP] = f32_to_bf16x2(pairmx[0], pairmx[1]);
                     __builtin_amdgcn_wave_barrier();
                     static_for<4>([&](auto q) {
                         constexpr int SUB = decltype(q)::value / 2, T = decltype(q)::value % 2, IA = 2 * IP + SUB;
@@ -217,34 +289,17 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
                         store16_sbase<0>(ot.base + (size_t)IA * ot.rowblk + (T ? (ot.rowblk >> 1) : 0), vofs, v, ot.stream);
                     });
                     __builtin_amdgcn_wave_barrier();
-                    if constexpr (EPI == EPI_ROWMAX && (IP & 1) == 1) {
-                        // Row maximum of the STORED values (Sec. 6.3.1): rounding to nearest even is monotonic, so it is the
-                        // rounded maximum of the fp32 results.  The four lanes of a row combine; lane 16 g + c then carries row c
-                        // of row block g: 64 rows are folded into the P(max) vector by one pair of atomic instructions.
-                        float r[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const uint32_t x = __float_as_uint(rmx[i]);
-                            const auto a = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-                            const uint32_t m = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
-                            const auto b = __builtin_amdgcn_permlane16_swap(m, m, false, false);
-                            r[i] = fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
-                        }
-                        float vmax = g == 0 ? r[0] : g == 1 ? r[1] : g == 2 ? r[2] : r[3];
-                        vmax = bf16_to_f32(f32_to_bf16(vmax)) + 0.0f;
-                        float* dst = ot.rowmax + (IP / 2) * 64 + ln;
-                        // signed max for non-negative values, unsigned min for negative ones (see atomic_max_f32_untracked);
-                        // both instructions always issue (the wait counts rely on it), each under its own lanes
-                        const uint64_t mp = __builtin_amdgcn_ballot_w64(vmax >= 0.0f), mn = __builtin_amdgcn_ballot_w64(vmax < 0.0f);   // NaN: neither
-                        asm volatile("s_mov_b64 exec, %2\n\tglobal_atomic_smax %0, %1, off\n\ts_mov_b64 exec, %3\n\tglobal_atomic_umin %0, %1, off\n\ts_mov_b64 exec, -1"
-                                     : : "v"(dst), "v"(vmax), "s"(mp), "s"(mn) : "memory");
-                    }
                 });
             }
             return;
         }
         // tiles cut by the matrix edge or with unaligned rows: element by element, guarded, then a full drain
         OutT* C = reinterpret_cast<OutT*>(ot.base);
+        [[maybe_unused]] float runmax[8];
+        if constexpr (EPI == EPI_ROWMAX) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) runmax[q] = __uint_as_float((q & 1) ? (runpk[q >> 1] & 0xFFFF0000u) : (runpk[q >> 1] << 16));
+        }
         static_for<32>([&](auto idx) {
             constexpr int i = decltype(idx)::value / 4, j = decltype(idx)::value % 4;
             const int m = 16 * i + c;
@@ -253,12 +308,15 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
             static_for<4>([&](auto ridx) {
                 constexpr int r = decltype(ridx)::value;
                 const float v = mfma_epilogue<EPI>(acc[i][j][r]);
-                if (m < ot.rows_left && nb + r < ot.cols_left) {
-                    store_out_untracked(cp, (int64_t)r, v);
-                    if constexpr (EPI == EPI_ROWMAX) atomic_max_f32_untracked(ot.rowmax + m, bf16_to_f32(f32_to_bf16(v)));
-                }
+                if (m < ot.rows_left && nb + r < ot.cols_left) store_out_untracked(cp, (int64_t)r, v);
+                // columns past the matrix edge stay out of the row maximum; rows past it are masked when it is flushed
+                if constexpr (EPI == EPI_ROWMAX) runmax[i] = max3f(runmax[i], nb + r < ot.cols_left ? v : -__builtin_inff(), -__builtin_inff());
             });
         });
+        if constexpr (EPI == EPI_ROWMAX) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) runpk[q] = f32_to_bf16x2(runmax[2 * q], runmax[2 * q + 1]);
+        }
         __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
     };
 
@@ -313,13 +371,13 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
         constexpr int EPV = 16 / (int)sizeof(OutT);
         OutTile ot;
         ot.base = static_cast<char*>(s.c) + ((int64_t)(m0 + wm * TM) * s.ldc + (n0 + wn * TN)) * (int64_t)sizeof(OutT);
-        ot.rowmax = s.rowmax + (m0 + wm * TM);
         ot.rowblk = (uint32_t)s.ldc * (16u * (uint32_t)sizeof(OutT));
         ot.ldc = s.ldc;
         ot.stream = ((int64_t)s.ldc * (int64_t)sizeof(OutT)) % 128 == 0;
         ot.whole = m0 + BM <= s.m && n0 + BN <= s.n && s.ldc % EPV == 0;
         ot.rows_left = s.m - (m0 + wm * TM);
         ot.cols_left = s.n - (n0 + wn * TN);
+        ot.rows_key = __builtin_amdgcn_readfirstlane(((tc.g << 16) | tc.tile_m) + 1);
         return ot;
     };
 
@@ -371,6 +429,9 @@ __global__ __launch_bounds__(512) void gemm_pingpong_kernel(GemmPlan p, int tm, 
         cv = nv;
     }
     if (pend) store_tile(prev);
+    if constexpr (EPI == EPI_ROWMAX) {
+        if (run_key) flush_rowmax();
+    }
     if (grp == 0) __builtin_amdgcn_s_barrier();   // pairs with the last barrier of waves 4-7
     __builtin_amdgcn_s_waitcnt(0x0070);           // trailing loads must land before LDS is released; stores drain
 }
