@@ -61,6 +61,8 @@ def parse():
     ap.add_argument("--stagger", type=int, default=4096, help="bytes between consecutive shard buffers with --layout staggered")
     ap.add_argument("--workload", default="mlp", choices=["mlp", "dp_grad", "classifier", "relayout", "uvw", "zero", "across", "clock_probe", "mfma_probe", "vendor_gemm", "tiny", "grid"],
                     help="mlp (default) is the workload the headline metric is quoted on")
+    ap.add_argument("--dense-logits", action="store_true",
+                    help="classifier workload: logits and gradient rows back to back (pitch 125000) instead of padded to 128 bytes")
     ap.add_argument("--calibrate", action="store_true",
                     help="before the timed region run ONE plain copy of known size (identity boxing B->B of the "
                          "1 GiB fp32 tensor: 1 GiB read + 1 GiB written) so that a counter run has a reference dispatch")
@@ -356,16 +358,21 @@ def bench_classifier(args, cfg, sbp, wl, torch, np):
     w_sh = arena([(Dm, Ci)] * k, torch.int16)
     for i in range(k):
         w_sh[i].copy_(bits(cfg["W"], cols=np.arange(*shard_range(C, k, i))))
-    l_sh = arena([(R, Ci)] * k, torch.int16)
+    # Row pitch of the logits and of their gradient: 125000 bf16 = 250000 bytes would put seven of eight rows across
+    # cache-line boundaries; the buffers are allocated with the pitch rounded up to 128 bytes (125056 elements) and
+    # passed with that leading dimension.  --dense-logits times the unpadded layout.
+    P = Ci if args.dense_logits else (Ci + 63) // 64 * 64
+    LD = 0 if P == Ci else P
+    l_sh = arena([(R, P)] * k, torch.int16)
     vec = lambda: arena([(R, 1)] * k, torch.float32)      # noqa: E731
     Ft, Wt = sbp.SbpTensor(f_sh, R, Dm, sbp.BF16), sbp.SbpTensor(w_sh, Dm, C, sbp.BF16)
-    L = sbp.SbpTensor(l_sh, R, C, sbp.BF16)
+    L = sbp.SbpTensor(l_sh, R, C, sbp.BF16, 0, LD)
     MP, MP2, MB, SP, SB, LP, LB, GR = (sbp.SbpTensor(vec(), R, 1, sbp.F32) for _ in range(8))
     for t in GR.keep:
         t.fill_(1.0 / R)
     labels = torch.from_numpy((wl.uniform(seed, 7, (R, 1), 0.0, float(C)).astype(np.int64) % C).astype(np.int32)).cuda()
     Y = sbp.SbpTensor([labels] * k, R, 1, sbp.I32)
-    DL = sbp.SbpTensor(arena([(R, Ci)] * k, torch.int16), R, C, sbp.BF16)
+    DL = sbp.SbpTensor(arena([(R, P)] * k, torch.int16), R, C, sbp.BF16, 0, LD)
 
     def stages_of(s):
         return [lambda st: sbp.sbp_matmul_rowmax(Ft, sbp.B, Wt, sbp.S(1), L, sbp.S(1), MP, k, st),     # logits + local row max
@@ -392,12 +399,13 @@ def bench_classifier(args, cfg, sbp, wl, torch, np):
                "boxing_psum_us": round(ms[4] * 1e3, 1),
                "xent_loss_us": round(ms[5] * 1e3, 1), "boxing_loss_us": round(ms[6] * 1e3, 1),
                "xent_grad_ms": round(ms[7], 4), "xent_grad_gbps": round(2 * lbytes / ms[7] / 1e6, 1),
-               "mean_loss": float(LB.keep[0].mean())}
+               "mean_loss": float(LB.keep[0].mean()), "logits_row_pitch_elements": P}
     roof = {"bound": "mfma", "kernel": "sbp_matmul (B,S1)->S1 bf16 logits", "achieved": round(tf, 2),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}
     wall -= ms[1]     # the comparison pass is not part of the step
     return result_line(args, "model-parallel classifier head, k=8: F[1024,512] B x W[512,1000000] S(1) -> bf16 logits S(1) with fused "
-                             "row max P(max)->B; sum exp(L - max) P(sum)->B; sparse cross entropy loss P(sum)->B and gradient S(1)",
+                             "row max P(max)->B; sum exp(L - max) P(sum)->B; sparse cross entropy loss P(sum)->B and gradient S(1); "
+                             f"logits row pitch {P} elements",
                        k, flops / (wall * 1e-3) / 1e12, "TFLOP/s", wall, kernels, roof)
 
 

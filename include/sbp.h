@@ -75,6 +75,15 @@ typedef struct sbp_tensor {
     int64_t rows, cols; /* GLOBAL shape; vectors are [n, 1]                           */
     int32_t dtype;      /* SBP_F32 | SBP_BF16 (SBP_I32 for label vectors)             */
     int32_t trans;      /* 0: shards hold the local tensor; 1: its transpose          */
+    int64_t ld;         /* row pitch of every stored local buffer in elements, 0 = dense
+                           (the stored row length).  Must be at least the longest stored row of
+                           any shard (SBP_ERR_SHAPE otherwise); the bytes between a row's end and
+                           the next row are never read or written.  A pitch that is a multiple of
+                           128 bytes keeps every row on cache-line boundaries (the classifier's
+                           125000-column logits shards: pitch 125056).  Accepted by sbp_matmul,
+                           sbp_matmul_ex, sbp_matmul_rowmax, sbp_row_max, sbp_row_sumexp,
+                           sbp_xent_loss and sbp_xent_grad; the boxing and the two-dimensional
+                           entry points take dense tensors only (SBP_ERR_UNSUPPORTED).          */
 } sbp_tensor_t;
 
 /* ---- epilogues of sbp_matmul_ex -------------------------------------------*/

@@ -37,7 +37,7 @@ EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex",
 class _CTensor(ctypes.Structure):
     _fields_ = [("shard", ctypes.POINTER(ctypes.c_void_p)),
                 ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
-                ("dtype", ctypes.c_int32), ("trans", ctypes.c_int32)]
+                ("dtype", ctypes.c_int32), ("trans", ctypes.c_int32), ("ld", ctypes.c_int64)]
 
 
 class SbpError(RuntimeError):
@@ -98,17 +98,18 @@ def lib() -> ctypes.CDLL:
 
 
 class SbpTensor:
-    """A global tensor as the ABI sees it: k device pointers + global shape + dtype + trans.
+    """A global tensor as the ABI sees it: k device pointers + global shape + dtype + trans + row pitch
+    (`ld` elements between stored rows, 0 = dense).
 
     `shards` are integers (device addresses) or objects with .data_ptr() (torch tensors); the
     object keeps them alive.  Nothing is copied."""
 
-    def __init__(self, shards: Sequence, rows: int, cols: int, dtype: int, trans: int = 0):
+    def __init__(self, shards: Sequence, rows: int, cols: int, dtype: int, trans: int = 0, ld: int = 0):
         self.keep = list(shards)
         ptrs = [s if isinstance(s, int) or s is None else s.data_ptr() for s in shards]
         self.k = len(ptrs)
         self._arr = (ctypes.c_void_p * max(1, self.k))(*ptrs)
-        self.c = _CTensor(ctypes.cast(self._arr, ctypes.POINTER(ctypes.c_void_p)), rows, cols, dtype, trans)
+        self.c = _CTensor(ctypes.cast(self._arr, ctypes.POINTER(ctypes.c_void_p)), rows, cols, dtype, trans, ld)
 
     def ref(self):
         return ctypes.byref(self.c)

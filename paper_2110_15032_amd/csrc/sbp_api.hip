@@ -25,15 +25,22 @@ Local local_of(int64_t rows, int64_t cols, sbp_t s, int32_t k, int32_t i) {
     return {rows, cols};
 }
 
-int32_t check_tensor(const sbp_tensor_t* t, sbp_t s, int32_t k) {
+// row pitch of a stored local buffer in elements: the descriptor's, or the stored row length
+int64_t pitch_of(const sbp_tensor_t* t, const Local& l) { return t->ld ? t->ld : (t->trans ? l.rows : l.cols); }
+
+// with_ld: the entry point takes a row pitch (sbp_tensor_t::ld); the others want dense tensors
+int32_t check_tensor(const sbp_tensor_t* t, sbp_t s, int32_t k, bool with_ld = false) {
     if (!t || !t->shard) return SBP_ERR_NULL;
-    if (t->rows < 0 || t->cols < 0) return SBP_ERR_SHAPE;
+    if (t->rows < 0 || t->cols < 0 || t->ld < 0) return SBP_ERR_SHAPE;
     if (t->dtype != SBP_F32 && t->dtype != SBP_BF16) return SBP_ERR_DTYPE;
     if (t->trans != 0 && t->trans != 1) return SBP_ERR_SHAPE;
     if (!is_sbp(s)) return SBP_ERR_AXIS;
+    if (t->ld && !with_ld) return SBP_ERR_UNSUPPORTED;
+    if (t->ld > INT32_MAX) return SBP_ERR_UNSUPPORTED;
     for (int32_t i = 0; i < k; ++i) {
         const Local l = local_of(t->rows, t->cols, s, k, i);
         if (l.rows * l.cols == 0) continue;  // an empty local tensor needs no storage
+        if (t->ld && (t->trans ? l.rows : l.cols) > t->ld) return SBP_ERR_SHAPE;
         if (!t->shard[i]) return SBP_ERR_NULL;
         if (reinterpret_cast<uintptr_t>(t->shard[i]) & 15u) return SBP_ERR_ALIGN;
     }
@@ -46,8 +53,10 @@ struct Span {
 void spans_of(const sbp_tensor_t* t, sbp_t s, int32_t k, std::vector<Span>& v) {
     for (int32_t i = 0; i < k; ++i) {
         const Local l = local_of(t->rows, t->cols, s, k, i);
-        const uintptr_t bytes = (uintptr_t)(l.rows * l.cols) * elem_bytes(t->dtype);
-        if (bytes == 0) continue;
+        if (l.rows * l.cols == 0) continue;
+        // stored as nrow rows of ncol elements, pitch_of() apart: the span ends with the last row's last element
+        const int64_t nrow = t->trans ? l.cols : l.rows, ncol = t->trans ? l.rows : l.cols;
+        const uintptr_t bytes = (uintptr_t)((nrow - 1) * pitch_of(t, l) + ncol) * elem_bytes(t->dtype);
         const uintptr_t lo = reinterpret_cast<uintptr_t>(t->shard[i]);
         v.push_back({lo, lo + bytes});
     }
@@ -68,7 +77,7 @@ int32_t check_tensor2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t
     if (!t || !t->shard || !s) return SBP_ERR_NULL;
     if (t->rows < 0 || t->cols < 0) return SBP_ERR_SHAPE;
     if (t->dtype != SBP_F32 && t->dtype != SBP_BF16) return SBP_ERR_DTYPE;
-    if (t->trans != 0) return SBP_ERR_UNSUPPORTED;
+    if (t->trans != 0 || t->ld != 0) return SBP_ERR_UNSUPPORTED;
     if (!is_sbp(s[0]) || !is_sbp(s[1])) return SBP_ERR_AXIS;
     for (int32_t a = 0; a < k0; ++a)
         for (int32_t b = 0; b < k1; ++b) {
@@ -182,9 +191,9 @@ static int32_t matmul_impl(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* 
     if (sy == SBP_AUTO) sy = deduced;
     if (!is_sbp(sy)) return SBP_ERR_AXIS;
     if (sy != deduced) return SBP_ERR_SIGNATURE;
-    if ((st = check_tensor(x, sx, k)) != SBP_OK) return st;
-    if ((st = check_tensor(w, sw, k)) != SBP_OK) return st;
-    if ((st = check_tensor(y, sy, k)) != SBP_OK) return st;
+    if ((st = check_tensor(x, sx, k, true)) != SBP_OK) return st;
+    if ((st = check_tensor(w, sw, k, true)) != SBP_OK) return st;
+    if ((st = check_tensor(y, sy, k, true)) != SBP_OK) return st;
     if (x->cols != w->rows || y->rows != x->rows || y->cols != w->cols) return SBP_ERR_SHAPE;
     // a P(sum) operand is fp32; its partner may be fp32 or bf16 (rows 4 and 5 of Table 1 inside a bf16 graph)
     int32_t f32_operand = 0;
@@ -244,9 +253,9 @@ static int32_t matmul_impl(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* 
         g.m = (int32_t)lx.rows;
         g.n = (int32_t)lw.cols;
         g.kk = (int32_t)lx.cols;
-        g.lda = (int32_t)(x->trans ? lx.rows : lx.cols);
-        g.ldb = (int32_t)(w->trans ? lw.rows : lw.cols);
-        g.ldc = (int32_t)ly.cols;
+        g.lda = (int32_t)pitch_of(x, lx);
+        g.ldb = (int32_t)pitch_of(w, lw);
+        g.ldc = (int32_t)pitch_of(y, ly);
         g.rowmax = rowmax ? static_cast<float*>(rowmax->shard[i]) : nullptr;
     }
     if (!rowmax) return launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
@@ -264,7 +273,9 @@ static int32_t matmul_impl(const sbp_tensor_t* x, sbp_t sx, const sbp_tensor_t* 
         rs.logits[i] = y->shard[i];
         rs.gmax[i] = nullptr;
         rs.out[i] = static_cast<float*>(rowmax->shard[i]);
-        rs.cols[i] = (int32_t)local_of(y->rows, y->cols, sy, k, i).cols;
+        const Local ly = local_of(y->rows, y->cols, sy, k, i);
+        rs.cols[i] = (int32_t)ly.cols;
+        rs.ld[i] = (int32_t)pitch_of(y, ly);
     }
     return launch_row_stat(rs, false, static_cast<hipStream_t>(stream));
 }
@@ -506,7 +517,7 @@ static int32_t row_stat(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t
     if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
     if (!logits || !out || (sumexp && !gmax)) return SBP_ERR_NULL;
     int32_t st;
-    if ((st = check_tensor(logits, sl, k)) != SBP_OK) return st;
+    if ((st = check_tensor(logits, sl, k, true)) != SBP_OK) return st;
     if (is_partial(sl)) return SBP_ERR_SIGNATURE;  // row statistics of an un-reduced partial are meaningless
     if (sl != SBP_S(1)) return SBP_ERR_UNSUPPORTED;  // only the model-parallel case yields partial vectors
     const sbp_t s_out = sumexp ? SBP_P_SUM : SBP_P_MAX;
@@ -531,7 +542,9 @@ static int32_t row_stat(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t
         plan.logits[i] = logits->shard[i];
         plan.gmax[i] = sumexp ? static_cast<const float*>(gmax->shard[i]) : nullptr;
         plan.out[i] = static_cast<float*>(out->shard[i]);
-        plan.cols[i] = (int32_t)local_of(logits->rows, logits->cols, sl, k, i).cols;
+        const Local l = local_of(logits->rows, logits->cols, sl, k, i);
+        plan.cols[i] = (int32_t)l.cols;
+        plan.ld[i] = (int32_t)pitch_of(logits, l);
     }
     return launch_row_stat(plan, sumexp, static_cast<hipStream_t>(stream));
 }
@@ -560,7 +573,7 @@ static int32_t xent(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* la
     if (k < 1 || k > SBP_MAX_K) return SBP_ERR_K;
     if (!logits || !labels || !gmax || !denom || !out) return SBP_ERR_NULL;
     int32_t st;
-    if ((st = check_tensor(logits, sl, k)) != SBP_OK) return st;
+    if ((st = check_tensor(logits, sl, k, true)) != SBP_OK) return st;
     if (sl != SBP_S(1)) return is_partial(sl) ? SBP_ERR_SIGNATURE : SBP_ERR_UNSUPPORTED;
     if (k > XENT_MAX_K) return SBP_ERR_UNSUPPORTED;
     if (logits->trans) return SBP_ERR_UNSUPPORTED;
@@ -577,7 +590,7 @@ static int32_t xent(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* la
     spans_of_vector(denom, k, ins);
     if (grad) {
         spans_of_vector(grad, k, ins);
-        if ((st = check_tensor(out, SBP_S(1), k)) != SBP_OK) return st;
+        if ((st = check_tensor(out, SBP_S(1), k, true)) != SBP_OK) return st;
         if (out->rows != R || out->cols != logits->cols || out->dtype != logits->dtype || out->trans) return SBP_ERR_SHAPE;
         spans_of(out, SBP_S(1), k, outs);
     } else {
@@ -599,6 +612,8 @@ static int32_t xent(const sbp_tensor_t* logits, sbp_t sl, const sbp_tensor_t* la
         plan.grad[i] = grad ? static_cast<const float*>(grad->shard[i]) : nullptr;
         plan.out[i] = out->shard[i];
         plan.cols[i] = (int32_t)split_len(logits->cols, k, i);
+        plan.ld[i] = logits->ld ? (int32_t)logits->ld : plan.cols[i];
+        plan.ld_out[i] = (grad && out->ld) ? (int32_t)out->ld : plan.cols[i];
         plan.begin[i] = (int32_t)split_begin(logits->cols, k, i);
     }
     return grad ? launch_xent_grad(plan, static_cast<hipStream_t>(stream)) : launch_xent_loss(plan, static_cast<hipStream_t>(stream));

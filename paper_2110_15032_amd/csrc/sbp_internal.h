@@ -92,7 +92,8 @@ struct RowStatPlan {
     const void* logits[SBP_MAX_K];
     const float* gmax[SBP_MAX_K];   // null for the max pass
     float* out[SBP_MAX_K];
-    int32_t cols[SBP_MAX_K];        // local column count of every shard (= row pitch)
+    int32_t cols[SBP_MAX_K];        // local column count of every shard
+    int32_t ld[SBP_MAX_K];          // row pitch of every shard, elements
     int64_t rows;
     int32_t k;
     int32_t dtype;
@@ -106,7 +107,9 @@ struct XentPlan {
     const float* denom[XENT_MAX_K];
     const float* grad[XENT_MAX_K];   // backward only
     void* out[XENT_MAX_K];           // loss partials (f32) or dlogits (dtype)
-    int32_t cols[XENT_MAX_K];        // local column count (= row pitch)
+    int32_t cols[XENT_MAX_K];        // local column count
+    int32_t ld[XENT_MAX_K];          // row pitch of the logits, elements
+    int32_t ld_out[XENT_MAX_K];      // row pitch of dlogits (backward only)
     int32_t begin[XENT_MAX_K];       // first global column of the shard
     int64_t rows;
     int32_t total_cols;

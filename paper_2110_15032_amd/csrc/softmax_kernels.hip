@@ -44,7 +44,7 @@ __global__ __launch_bounds__(RS_THREADS) void row_stat_kernel(RowStatPlan p) {
     float acc = ident;
     if (cols > 0) {
         constexpr int EPV = BF16 ? 8 : 4;  // elements per 16-byte vector
-        const char* base = static_cast<const char*>(p.logits[shard]) + (int64_t)row * cols * (BF16 ? 2 : 4);
+        const char* base = static_cast<const char*>(p.logits[shard]) + (int64_t)row * p.ld[shard] * (BF16 ? 2 : 4);
         // rows start 16-byte aligned only when the pitch is a multiple of EPV; otherwise peel
         const int32_t mis = (int32_t)((reinterpret_cast<uintptr_t>(base) & 15u) / (BF16 ? 2 : 4));
         int32_t head = mis ? EPV - mis : 0;
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(RS_THREADS) void xent_loss_kernel(XentPlan p) {
     const int32_t c = p.labels[i][r] - p.begin[i];
     float out = 0.0f;
     if (c >= 0 && c < p.cols[i]) {
-        const int64_t pos = r * p.cols[i] + c;
+        const int64_t pos = r * p.ld[i] + c;
         float l;
         if constexpr (BF16) l = __uint_as_float((uint32_t) static_cast<const uint16_t*>(p.logits[i])[pos] << 16);
         else l = static_cast<const float*>(p.logits[i])[pos];
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(RS_THREADS) void xent_grad_kernel(XentPlan p) {
         const float g = live ? p.grad[i][r] : 0.0f;
         const float m = p.gmax[i][r], inv = 1.0f / p.denom[i][r];
         const int32_t yc = y - p.begin[i] - (int32_t)c;   // position of the label inside this group, if any
-        const int64_t pos = (int64_t)r * p.cols[i] + c;
+        const int64_t pos = (int64_t)r * p.ld[i] + c, opos = (int64_t)r * p.ld_out[i] + c;
         float v[VE];
         if constexpr (BF16 && VE == 8) {
             const u32x4 w = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.logits[i]) + pos);
@@ -154,13 +154,13 @@ __global__ __launch_bounds__(RS_THREADS) void xent_grad_kernel(XentPlan p) {
         for (int e = 0; e < VE; ++e) v[e] = (__expf(v[e] - m) * inv - (e == yc ? 1.0f : 0.0f)) * g;
         if constexpr (BF16 && VE == 8) {
             const u32x4 o = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
-            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.out[i]) + pos));
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.out[i]) + opos));
         } else if constexpr (!BF16 && VE == 4) {
             const f32x4 o = {v[0], v[1], v[2], v[3]};
-            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(static_cast<float*>(p.out[i]) + pos));
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(static_cast<float*>(p.out[i]) + opos));
         } else {
-            if constexpr (BF16) static_cast<uint16_t*>(p.out[i])[pos] = (uint16_t)(pack_bf16(v[0], 0.0f) & 0xFFFFu);
-            else static_cast<float*>(p.out[i])[pos] = v[0];
+            if constexpr (BF16) static_cast<uint16_t*>(p.out[i])[opos] = (uint16_t)(pack_bf16(v[0], 0.0f) & 0xFFFFu);
+            else static_cast<float*>(p.out[i])[opos] = v[0];
         }
     }
 }
@@ -184,7 +184,7 @@ int32_t launch_xent_grad(const XentPlan& plan, hipStream_t stream) {
     bool vec = true;
     int64_t max_units = 0;
     for (int i = 0; i < plan.k; ++i) {
-        if (plan.cols[i] % epv) vec = false;
+        if (plan.cols[i] % epv || plan.ld[i] % epv || plan.ld_out[i] % epv) vec = false;
         max_units = plan.cols[i] > max_units ? plan.cols[i] : max_units;
     }
     max_units = max_units * plan.rows / (vec ? epv : 1);

@@ -55,34 +55,58 @@ def abi_dtype(np_dtype) -> int:
     return sbp.BF16 if np.dtype(np_dtype) == np.uint16 else sbp.F32
 
 
-class DevTensor:
-    """k device shards of one global tensor + the ABI descriptor"""
+POISON = {np.dtype(np.float32): np.float32(np.nan), np.dtype(np.uint16): np.uint16(0x7FC1), np.dtype(np.uint32): np.uint32(0x7FC00001)}
 
-    def __init__(self, shards_dev, rows, cols, np_dtype, sbp_sig, trans=0):
+
+class DevTensor:
+    """k device shards of one global tensor + the ABI descriptor.  ld > 0: every stored local buffer has that row
+    pitch (elements); the padding is poisoned on upload and host() asserts that it still is (never written)."""
+
+    def __init__(self, shards_dev, rows, cols, np_dtype, sbp_sig, trans=0, ld=0, stored_shapes=None):
         self.dev = list(shards_dev)
         self.rows, self.cols = rows, cols
         self.np_dtype = np.dtype(np_dtype)
         self.sig = sbp_sig
         self.trans = trans
-        self.desc = sbp.SbpTensor(self.dev, rows, cols, abi_dtype(np_dtype), trans)
+        self.ld = ld
+        self.stored_shapes = stored_shapes     # (rows, cols) of every stored buffer, needed with ld
+        self.desc = sbp.SbpTensor(self.dev, rows, cols, abi_dtype(np_dtype), trans, ld)
 
     @property
     def k(self):
         return len(self.dev)
 
-    @classmethod
-    def from_host(cls, shards: list[np.ndarray], rows, cols, sig, trans=0):
-        """shards are the LOGICAL local tensors; trans=1 stores each transposed"""
-        dev = [upload(s.T if trans else s) for s in shards]
-        return cls(dev, rows, cols, shards[0].dtype, sig, trans)
+    @staticmethod
+    def _padded(a: np.ndarray, ld: int) -> np.ndarray:
+        a = np.ascontiguousarray(a)
+        out = np.full((a.shape[0], ld), POISON[a.dtype], dtype=a.dtype)
+        out[:, :a.shape[1]] = a
+        return out
 
     @classmethod
-    def empty(cls, rows, cols, np_dtype, sig, k):
+    def from_host(cls, shards: list[np.ndarray], rows, cols, sig, trans=0, ld=0):
+        """shards are the LOGICAL local tensors; trans=1 stores each transposed"""
+        stored = [np.ascontiguousarray(s.T if trans else s) for s in shards]
+        dev = [upload(cls._padded(s, ld) if ld else s) for s in stored]
+        return cls(dev, rows, cols, shards[0].dtype, sig, trans, ld, [s.shape for s in stored])
+
+    @classmethod
+    def empty(cls, rows, cols, np_dtype, sig, k, ld=0):
         shapes = [orc.local_shape(rows, cols, sig, k, i) for i in range(k)]
-        return cls([empty_dev(s, np_dtype) for s in shapes], rows, cols, np_dtype, sig)
+        dev = [empty_dev((s[0], ld) if ld else s, np_dtype) for s in shapes]
+        return cls(dev, rows, cols, np_dtype, sig, 0, ld, shapes)
 
     def host(self) -> list[np.ndarray]:
         out = [download(t, self.np_dtype) for t in self.dev]
+        if self.ld:
+            cut = []
+            for o, (r, c) in zip(out, self.stored_shapes):
+                o = o.reshape(r, self.ld) if r else o.reshape(0, self.ld)
+                pad = o[:, c:]
+                want = np.full(pad.shape, POISON[self.np_dtype], dtype=self.np_dtype)
+                assert pad.tobytes() == want.tobytes(), "the padding between rows was written"
+                cut.append(np.ascontiguousarray(o[:, :c]))
+            out = cut
         return [o.T if self.trans else o for o in out]
 
 

@@ -156,7 +156,11 @@ def test_config3_dp_weight_gradient_full_size():
 
 
 # ----------------------------------------------------------------------------------------------
-def test_config4_classifier_head_full_size():
+@pytest.mark.parametrize("layout", ["pitch128", "dense"])
+def test_config4_classifier_head_full_size(layout):
+    """layout pitch128: the logits and their gradient have a row pitch of 125056 elements (whole 128-byte lines,
+    what bench.py times); dense: 125000, seven of eight rows straddle cache lines.  The padded form sends every
+    row through the oracle, the dense one a sample."""
     torch = torch_mod()
     cfg = CONFIGS["classifier"]
     k = cfg["k"]
@@ -168,11 +172,18 @@ def test_config4_classifier_head_full_size():
     w_host = [bf16_window(cfg["W"], cols=np.arange(*orc.split_range(C, k, i))) for i in range(k)]   # [512, 125000] each
     w_sh = [dev_u16(w) for w in w_host]
     Ci = C // k
-    l_sh = [torch.full((R, Ci), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    P = (Ci + 63) // 64 * 64 if layout == "pitch128" else Ci      # row pitch in elements
+    LD = P if P != Ci else 0
+
+    def logits_buffers():
+        store = [torch.full((R, P), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+        return store, [s[:, :Ci] for s in store]                  # the views start at the buffers' first element
+
+    l_store, l_sh = logits_buffers()
     vec = lambda: [torch.full((R, 1), float("nan"), device="cuda") for _ in range(k)]      # noqa: E731
     mp, mb, sp, sb = vec(), vec(), vec(), vec()
     Ft, Wt = sbp.SbpTensor(f_sh, R, Dm, sbp.BF16), sbp.SbpTensor(w_sh, Dm, C, sbp.BF16)
-    L = sbp.SbpTensor(l_sh, R, C, sbp.BF16)
+    L = sbp.SbpTensor(l_sh, R, C, sbp.BF16, 0, LD)
     MP, MB, SP, SB = (sbp.SbpTensor(v, R, 1, sbp.F32) for v in (mp, mb, sp, sb))
     sbp.sbp_matmul(Ft, sbp.B, Wt, sbp.S(1), L, sbp.S(1), k)
     sbp.sbp_row_max(L, sbp.S(1), MP, k)
@@ -198,7 +209,7 @@ def test_config4_classifier_head_full_size():
     del lf
 
     # (a) sampled feature rows through the oracle (all 10^6 classes of each), shard by shard
-    rows = np.arange(R) if FULL else tile_rows(R, 256, 3, 11)
+    rows = np.arange(R) if (FULL and layout == "pitch128") else tile_rows(R, 256, 3, 11)
     print(f"config 4: {len(rows)} of {R} feature rows through the oracle", flush=True)
     Fr = orc.bf16_to_f64(Fw[rows])
     ridx = torch.from_numpy(rows).cuda()
@@ -222,15 +233,16 @@ def test_config4_classifier_head_full_size():
 
     # ---- the form bench.py times: row max folded into the logits GEMM; then the sparse cross entropy ----
     print("config 4: fused row max, cross entropy loss and gradient at full size", flush=True)
-    l2_sh = [torch.full((R, Ci), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    l2_store, l2_sh = logits_buffers()
     mp2 = vec()
-    L2, MP2 = sbp.SbpTensor(l2_sh, R, C, sbp.BF16), sbp.SbpTensor(mp2, R, 1, sbp.F32)
+    L2, MP2 = sbp.SbpTensor(l2_sh, R, C, sbp.BF16, 0, LD), sbp.SbpTensor(mp2, R, 1, sbp.F32)
     sbp.sbp_matmul_rowmax(Ft, sbp.B, Wt, sbp.S(1), L2, sbp.S(1), MP2, k)
     sync()
     for i in range(k):
         assert torch.equal(l2_sh[i], l_sh[i]), f"logits of the fused call, shard {i}"
         assert torch.equal(mp2[i], mp[i]), f"fused row max, shard {i}"
-    del l2_sh, L2
+        assert bool((l2_store[i][:, Ci:] == 0x7FC1).all()), f"padding of the logits, shard {i}"
+    del l2_sh, l2_store, L2
 
     y_host = (wl.uniform(SEED, 40, (R, 1), 0.0, float(C)).astype(np.int64) % C).astype(np.int32)
     y_host[5, 0] = -1                                   # ignored rows
@@ -239,15 +251,18 @@ def test_config4_classifier_head_full_size():
     y_dev = torch.from_numpy(y_host).cuda()
     g_dev = torch.from_numpy(g_host).cuda()
     lp, lb = vec(), vec()
-    dl_sh = [torch.full((R, Ci), 0x7FC1, dtype=torch.int16, device="cuda") for _ in range(k)]
+    dl_store, dl_sh = logits_buffers()
     Y = sbp.SbpTensor([y_dev] * k, R, 1, sbp.I32)
     G = sbp.SbpTensor([g_dev] * k, R, 1, sbp.F32)
     LP, LB = sbp.SbpTensor(lp, R, 1, sbp.F32), sbp.SbpTensor(lb, R, 1, sbp.F32)
-    DL = sbp.SbpTensor(dl_sh, R, C, sbp.BF16)
+    DL = sbp.SbpTensor(dl_sh, R, C, sbp.BF16, 0, LD)
     sbp.sbp_xent_loss(L, sbp.S(1), Y, MB, SB, LP, k)
     sbp.sbp_boxing(LP, sbp.P_SUM, LB, sbp.B, k)
     sbp.sbp_xent_grad(L, sbp.S(1), Y, MB, SB, G, DL, k)
     sync()
+
+    for i in range(k):
+        assert bool((l_store[i][:, Ci:] == 0x7FC1).all()) and bool((dl_store[i][:, Ci:] == 0x7FC1).all()), f"padding, shard {i}"
 
     # (b) over the whole output on the device: loss = log s + m - L[r, y], gradient = g (exp(L - m) / s - onehot)
     valid = (y_dev[:, 0] >= 0) & (y_dev[:, 0] < C)

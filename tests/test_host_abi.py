@@ -64,16 +64,39 @@ def test_local_shape_uses_the_balanced_split(n, k):
 
 
 # ----------------------------------------------------------------------------- validation
-def fake(k, rows, cols, dtype=sbp.F32, base=0x10000000, step=0x1000000, trans=0):
+def fake(k, rows, cols, dtype=sbp.F32, base=0x10000000, step=0x1000000, trans=0, ld=0):
     """descriptor over made-up, well-aligned, non-overlapping addresses (never dereferenced:
     every call below must be rejected before a launch)"""
-    return sbp.SbpTensor([base + i * step for i in range(k)], rows, cols, dtype, trans)
+    return sbp.SbpTensor([base + i * step for i in range(k)], rows, cols, dtype, trans, ld)
 
 
 def status_of(fn, *a, **kw):
     with pytest.raises(sbp.SbpError) as e:
         fn(*a, **kw)
     return e.value.status
+
+
+def test_row_pitch_validation_errors():
+    """sbp_tensor_t::ld: at least the longest stored row, never negative, and only where the header allows it"""
+    k = 2
+    S0, S1, B_, P = sbp.S(0), sbp.S(1), sbp.B, sbp.P_SUM
+    x = fake(k, 8, 16)                                   # S(1): local [8, 8]
+    w = fake(k, 16, 8, base=0x20000000)                  # S(0): local [8, 8]
+    y = fake(k, 8, 8, base=0x30000000)
+    assert status_of(sbp.sbp_matmul, fake(k, 8, 16, ld=7), S1, w, S0, y, P, k, 0) == -3       # shorter than a stored row
+    assert status_of(sbp.sbp_matmul, x, S1, fake(k, 16, 8, base=0x20000000, ld=-8), S0, y, P, k, 0) == -3
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, fake(k, 8, 8, base=0x30000000, ld=4), P, k, 0) == -3
+    xt = fake(k, 8, 16, trans=1, ld=7)                   # stored [8 kk][8 m]: the stored row is the m extent
+    assert status_of(sbp.sbp_matmul, xt, S1, w, S0, y, P, k, 0) == -3
+    # a pitched output that would run into the next shard's buffer is an alias
+    tight = sbp.SbpTensor([0x30000000, 0x30000000 + 8 * 8 * 4], 8, 8, sbp.F32, 0, 12)
+    assert status_of(sbp.sbp_matmul, x, S1, w, S0, tight, P, k, 0) == -7
+    # boxing and the two-dimensional entry points take dense tensors only
+    t_in, t_out = fake(k, 8, 8, ld=16), fake(k, 8, 8, base=0x40000000)
+    assert status_of(sbp.sbp_boxing, t_in, S0, t_out, B_, k, 0) == -9
+    assert status_of(sbp.sbp_boxing, fake(k, 8, 8), S0, fake(k, 8, 8, base=0x40000000, ld=16), B_, k, 0) == -9
+    assert status_of(sbp.sbp_boxing_across, t_in, S0, k, t_out, B_, k, 0) == -9
+    assert status_of(sbp.sbp_boxing_cast, t_in, S0, fake(k, 8, 8, dtype=sbp.BF16, base=0x40000000), B_, k, 0) == -9
 
 
 def test_matmul_validation_errors():
