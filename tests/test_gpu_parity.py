@@ -329,6 +329,40 @@ def test_matmul_partial_fp32_times_bf16(row, tx, tw, shape, variant):
         assert_matmul_close(got[i], ref[i], 1e-5, f"row {row} trans=({tx},{tw}) shape={shape} variant={variant} partial {i}")
 
 
+def test_fused_row_max_of_the_pingpong_kernel_across_tiles_rows_and_shards():
+    """The ping-pong kernel carries the row maxima in registers from tile to tile and sends them to the P(max)
+    vector only when a workgroup moves to other rows or to another shard, or ends (Sec. 6.3.1, local maximum).
+    320 tiles over 256 workgroups: some walk two tiles, of the same rows or of different shards; the bottom tile
+    row is cut by the matrix edge (rows past it must not reach the vector) and so is the right tile column."""
+    k, M, K, N = 2, 3 * 256 + 40, 128, 2 * (39 * 256 + 24)
+    X, W = rnd_bf16(31, (M, K)), rnd_bf16(32, (K, N), 0.05)
+    X[M - 1, :] = np.uint16(0xBF80)              # last row -1: its maxima are negative in many column ranges
+    Xs, Ws = orc.scatter(X, orc.B, k), orc.scatter(W, orc.S1, k)
+    dx, dw = DevTensor.from_host(Xs, M, K, orc.B), DevTensor.from_host(Ws, K, N, orc.S1)
+    torch = __import__("torch")
+    res = {}
+    for variant in (21, 16):
+        y = DevTensor.empty(M, N, np.uint16, orc.S1, k)
+        m_big = [torch.full((M + 256,), float("nan"), device="cuda") for _ in range(k)]     # 256 guard entries behind the vector
+        m = sbp.SbpTensor(m_big, M, 1, sbp.F32)
+        sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, variant)
+        try:
+            sbp.sbp_matmul_rowmax(dx.desc, sbp.B, dw.desc, sbp.S(1), y.desc, sbp.AUTO, m, k)
+            sync()
+        finally:
+            sbp.sbp_set_knob(sbp.KNOB_GEMM_VARIANT, 0)
+        for b in m_big:
+            assert bool(torch.isnan(b[M:]).all()), f"variant {variant}: a row past the matrix edge reached the P(max) vector"
+        res[variant] = (y.host(), [b[:M].cpu().numpy().reshape(M, 1) for b in m_big])
+    ref, _ = orc.matmul_sbp([values(x) for x in Xs], orc.B, [values(w) for w in Ws], orc.S1)
+    for i in range(k):
+        assert_bits_equal(res[21][0][i], res[16][0][i], f"logits shard {i}: ping-pong against lockstep kernel")
+        assert_matmul_close(values(res[21][0][i]), ref[i], 2e-2, f"logits shard {i} vs oracle")
+        want = orc.row_max(values(res[21][0][i]))
+        assert np.array_equal(res[21][1][i][:, 0].astype(np.float64), want), f"row max shard {i} vs oracle"
+        assert np.array_equal(res[21][1][i], res[16][1][i]), f"row max shard {i}: ping-pong against lockstep kernel"
+
+
 def test_matmul_bf16_persistent_kernel_uneven_shards():
     """S(0) x B with M = 5 * 256 + 3 over k = 5: three shards of 257 rows (two tile-rows, the second
     one row high), two of 256 (one tile-row), so the tile list has holes the persistent walk must
