@@ -242,13 +242,23 @@ __device__ inline TileCoord map_tile(int bid, int nblk, int tm, int tn, int grou
     return t;
 }
 
+// max(a, b, c) in one instruction, a NaN operand ignored next to a number (the hardware's maxNum).  Written as
+// assembly because fmaxf() on values the compiler cannot prove canonical (matrix-instruction results) costs a
+// canonicalising multiply per operand: 300 instead of 64 vector instructions per tile and wave in the fused row
+// maximum.
+__device__ inline float max3f(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // gelu(x) = 0.5 x erfc(-x / sqrt 2), with erfc(z) = t 2^(-z^2 log2 e + P(t)), t = 1 / (1 + z / 2), for
 // z = |x| / sqrt 2 >= 0.  This is the form of the classic Chebyshev fit of erfc ("erfcc" in Numerical
 // Recipes), which keeps its RELATIVE accuracy in the tail, so gelu of a negative argument does too.
 // P is a degree-5 minimax fit of log2(erfc(z) e^(z^2) / t) on 0 <= z <= 14 made for this kernel (the
 // published fit has degree 9 and 1e-7; this one costs four FMAs less).  Relative error of gelu below
 // 2.2e-5 for every x whose result is a normal fp32 number, a hundredth of a bf16 rounding step.  One rcp,
-// one exp2, one max, eight FMA/mul, no branch, no select.
+// one exp2, one max (max3f: fmaxf would add a canonicalising instruction), eight FMA/mul, no branch, no select.
 // The argument is clamped to +-14 (erfc underflows before that), so +-inf give +inf and -0.
 __device__ inline float gelu_fast(float x) {
     const float xc = __builtin_amdgcn_fmed3f(x, -14.0f, 14.0f);
@@ -262,23 +272,13 @@ __device__ inline float gelu_fast(float x) {
     const float w = xc * 0.84932180028801905f;               // sqrt(log2(e) / 2): w^2 = z^2 log2 e
     const float e = t * __builtin_amdgcn_exp2f(fmaf(-w, w, p));   // 0.5 erfc(|x| / sqrt 2)
     // 0.5 x (1 + erf) = max(x, 0) - |x| 0.5 erfc(|x| / sqrt 2) for either sign; nothing cancels for x < 0
-    return fmaf(-fabsf(xc), e, fmaxf(x, 0.0f));
+    return fmaf(-fabsf(xc), e, max3f(x, 0.0f, 0.0f));
 }
 
 template <int EPI>
 __device__ inline float mfma_epilogue(float v) {
     if constexpr (EPI == SBP_EPI_GELU) return gelu_fast(v);
     else return v;
-}
-
-// max(a, b, c) in one instruction, a NaN operand ignored next to a number (the hardware's maxNum).  Written as
-// assembly because fmaxf() on values the compiler cannot prove canonical (matrix-instruction results) costs a
-// canonicalising multiply per operand: 300 instead of 64 vector instructions per tile and wave in the fused row
-// maximum.
-__device__ inline float max3f(float a, float b, float c) {
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
 }
 
 constexpr int STAGE_BYTES = 4096;

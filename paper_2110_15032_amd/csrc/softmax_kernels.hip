@@ -123,11 +123,22 @@ template <bool BF16, int VE>
 __global__ __launch_bounds__(RS_THREADS) void xent_grad_kernel(XentPlan p) {
     const int i = blockIdx.y;
     const uint32_t cols_v = (uint32_t)p.cols[i] / VE;
-    const uint64_t total = (uint64_t)p.rows * cols_v;
+    if (cols_v == 0) return;
+    // (row, vector) of this lane's first item by one division, then advanced by the grid stride with adds only:
+    // a 64-bit division per item costs more vector instructions than the item's arithmetic and made the kernel
+    // instruction-bound instead of memory-bound
     const uint64_t stride = (uint64_t)gridDim.x * RS_THREADS;
-    for (uint64_t idx = (uint64_t)blockIdx.x * RS_THREADS + threadIdx.x; idx < total; idx += stride) {
-        const uint32_t r = (uint32_t)(idx / cols_v);
-        const uint32_t c = (uint32_t)(idx - (uint64_t)r * cols_v) * VE;
+    const uint32_t dr = (uint32_t)(stride / cols_v), dc = (uint32_t)(stride % cols_v);
+    const uint64_t first = (uint64_t)blockIdx.x * RS_THREADS + threadIdx.x;
+    uint64_t r64 = first / cols_v;
+    uint32_t cv = (uint32_t)(first % cols_v);
+    for (; r64 < (uint64_t)p.rows; r64 += dr, cv += dc) {
+        if (cv >= cols_v) {
+            cv -= cols_v;
+            if (++r64 >= (uint64_t)p.rows) break;
+        }
+        const uint32_t r = (uint32_t)r64;
+        const uint32_t c = cv * VE;
         const int32_t y = p.labels[i][r];
         const bool live = y >= 0 && y < p.total_cols;
         const float g = live ? p.grad[i][r] : 0.0f;
