@@ -81,9 +81,9 @@ typedef struct sbp_tensor {
                            the next row are never read or written.  A pitch that is a multiple of
                            128 bytes keeps every row on cache-line boundaries (the classifier's
                            125000-column logits shards: pitch 125056).  Accepted by sbp_matmul,
-                           sbp_matmul_ex, sbp_matmul_rowmax, sbp_row_max, sbp_row_sumexp,
-                           sbp_xent_loss and sbp_xent_grad; the boxing and the two-dimensional
-                           entry points take dense tensors only (SBP_ERR_UNSUPPORTED).          */
+                           sbp_matmul_ex, sbp_matmul_rowmax, sbp_matmul_2d, sbp_row_max,
+                           sbp_row_sumexp, sbp_xent_loss and sbp_xent_grad; the boxing entry
+                           points take dense tensors only (SBP_ERR_UNSUPPORTED).                */
 } sbp_tensor_t;
 
 /* ---- epilogues of sbp_matmul_ex -------------------------------------------*/

@@ -73,16 +73,17 @@ int32_t check_grid(int32_t k0, int32_t k1) {
     if (k0 < 1 || k1 < 1 || (int64_t)k0 * k1 > SBP_MAX_K) return SBP_ERR_K;
     return SBP_OK;
 }
-int32_t check_tensor2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t k1) {
+int32_t check_tensor2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t k1, bool with_ld = false) {
     if (!t || !t->shard || !s) return SBP_ERR_NULL;
-    if (t->rows < 0 || t->cols < 0) return SBP_ERR_SHAPE;
+    if (t->rows < 0 || t->cols < 0 || t->ld < 0) return SBP_ERR_SHAPE;
     if (t->dtype != SBP_F32 && t->dtype != SBP_BF16) return SBP_ERR_DTYPE;
-    if (t->trans != 0 || t->ld != 0) return SBP_ERR_UNSUPPORTED;
+    if (t->trans != 0 || (t->ld != 0 && !with_ld) || t->ld > INT32_MAX) return SBP_ERR_UNSUPPORTED;
     if (!is_sbp(s[0]) || !is_sbp(s[1])) return SBP_ERR_AXIS;
     for (int32_t a = 0; a < k0; ++a)
         for (int32_t b = 0; b < k1; ++b) {
             const Local l = local_of2(t->rows, t->cols, s, k0, k1, a, b);
             if (l.rows * l.cols == 0) continue;
+            if (t->ld && l.cols > t->ld) return SBP_ERR_SHAPE;
             void* p = t->shard[a * k1 + b];
             if (!p) return SBP_ERR_NULL;
             if (reinterpret_cast<uintptr_t>(p) & 15u) return SBP_ERR_ALIGN;
@@ -93,8 +94,8 @@ void spans_of2(const sbp_tensor_t* t, const sbp_t* s, int32_t k0, int32_t k1, st
     for (int32_t a = 0; a < k0; ++a)
         for (int32_t b = 0; b < k1; ++b) {
             const Local l = local_of2(t->rows, t->cols, s, k0, k1, a, b);
-            const uintptr_t bytes = (uintptr_t)(l.rows * l.cols) * elem_bytes(t->dtype);
-            if (bytes == 0) continue;
+            if (l.rows * l.cols == 0) continue;
+            const uintptr_t bytes = (uintptr_t)((l.rows - 1) * pitch_of(t, l) + l.cols) * elem_bytes(t->dtype);
             const uintptr_t lo = reinterpret_cast<uintptr_t>(t->shard[a * k1 + b]);
             v.push_back({lo, lo + bytes});
         }
@@ -412,9 +413,9 @@ int32_t sbp_matmul_2d(const sbp_tensor_t* x, const sbp_t* sx, const sbp_tensor_t
             if (!is_sbp(sy_in[d])) return SBP_ERR_AXIS;
             if (sy_in[d] != sy[d]) return SBP_ERR_SIGNATURE;
         }
-    if ((st = check_tensor2(x, sx, k0, k1)) != SBP_OK) return st;
-    if ((st = check_tensor2(w, sw, k0, k1)) != SBP_OK) return st;
-    if ((st = check_tensor2(y, sy, k0, k1)) != SBP_OK) return st;
+    if ((st = check_tensor2(x, sx, k0, k1, true)) != SBP_OK) return st;
+    if ((st = check_tensor2(w, sw, k0, k1, true)) != SBP_OK) return st;
+    if ((st = check_tensor2(y, sy, k0, k1, true)) != SBP_OK) return st;
     if (x->cols != w->rows || y->rows != x->rows || y->cols != w->cols) return SBP_ERR_SHAPE;
     const bool px = is_partial(sx[0]) || is_partial(sx[1]), pw = is_partial(sw[0]) || is_partial(sw[1]);
     const bool py = is_partial(sy[0]) || is_partial(sy[1]);
@@ -456,9 +457,9 @@ int32_t sbp_matmul_2d(const sbp_tensor_t* x, const sbp_t* sx, const sbp_tensor_t
             g.m = (int32_t)lx.rows;
             g.n = (int32_t)lw.cols;
             g.kk = (int32_t)lx.cols;
-            g.lda = (int32_t)lx.cols;
-            g.ldb = (int32_t)lw.cols;
-            g.ldc = (int32_t)ly.cols;
+            g.lda = (int32_t)pitch_of(x, lx);
+            g.ldb = (int32_t)pitch_of(w, lw);
+            g.ldc = (int32_t)pitch_of(y, ly);
         }
     return launch_gemm(plan, g_gemm_variant.load(), static_cast<hipStream_t>(stream));
 }

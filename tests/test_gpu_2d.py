@@ -121,6 +121,44 @@ def test_matmul_2d_bf16_table3_on_the_matrix_cores(sx, sw):
     assert_matmul_close(orc.assemble2([values(g) for g in got], sy, k0, k1), orc.matmul(values(X), values(W)), 2e-2, "assembled")
 
 
+@pytest.mark.parametrize("sx,sw", TABLE3)
+def test_matmul_2d_bf16_with_row_pitch_equals_the_dense_call(sx, sw):
+    """the same products with every local buffer padded to a row pitch: bit-identical results, padding untouched"""
+    k0, k1 = 2, 4
+    M, K, N = 2 * 520, 4 * 256, 4 * 328
+    X, W = rnd_bf16(3, (M, K)), rnd_bf16(4, (K, N), 0.05)
+    Xs, Ws = orc.scatter2(X, sx, k0, k1), orc.scatter2(W, sw, k0, k1)
+    _, sy = orc.matmul_sbp2([values(x) for x in Xs], sx, [values(w) for w in Ws], sw)
+    out_dtype = np.float32 if P in sy else np.uint16
+    dx, dw = Dev2.from_host(Xs, M, K), Dev2.from_host(Ws, K, N)
+    dy = Dev2.empty(M, N, out_dtype, sy, k0, k1)
+    sbp.sbp_matmul_2d(dx.desc, abi2(sx), dw.desc, abi2(sw), dy.desc, abi2(sy), k0, k1)
+    sync()
+    dense = dy.host()
+
+    def padded(shards, pad, poison):
+        ld = max(s.shape[1] for s in shards) + pad
+        bufs = []
+        for s in shards:
+            b = np.full((s.shape[0], ld), poison, dtype=s.dtype)
+            b[:, :s.shape[1]] = s
+            bufs.append(upload(b))
+        return bufs, ld
+
+    xb, ldx = padded(Xs, 8, np.uint16(0x7FC1))
+    wb, ldw = padded(Ws, 24, np.uint16(0x7FC1))
+    yb, ldy = padded([np.zeros(d.shape, d.dtype) for d in dense], 16, np.float32(np.nan) if out_dtype == np.float32 else np.uint16(0x7FC1))
+    abi_dt = sbp.F32 if out_dtype == np.float32 else sbp.BF16
+    sbp.sbp_matmul_2d(sbp.SbpTensor(xb, M, K, sbp.BF16, 0, ldx), abi2(sx), sbp.SbpTensor(wb, K, N, sbp.BF16, 0, ldw), abi2(sw),
+                      sbp.SbpTensor(yb, M, N, abi_dt, 0, ldy), abi2(sy), k0, k1)
+    sync()
+    for i, (t, d) in enumerate(zip(yb, dense)):
+        full = download(t, np.dtype(out_dtype)).reshape(-1, ldy)
+        assert_bits_equal(np.ascontiguousarray(full[:, :d.shape[1]]), d, f"device {i}: pitched against dense")
+        pad = full[:, d.shape[1]:]
+        assert bool(np.isnan(pad).all()) if out_dtype == np.float32 else bool((pad == 0x7FC1).all()), f"device {i}: padding written"
+
+
 CONVERSIONS = [((S0, P), (S0, B)), ((S0, P), (S0, S1)), ((S0, S1), (S0, B)), ((S0, S1), (S0, S0)), ((S0, B), (S0, S1)),
                ((S0, B), (B, B)), ((B, S1), (S0, S1)), ((P, S1), (B, S1)), ((P, B), (S0, B)), ((S1, S0), (B, S0)),
                ((P, P), (P, B)), ((S0, B), (S0, P)), ((S1, B), (S0, B))]
