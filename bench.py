@@ -634,10 +634,12 @@ def bench_mfma_probe(args, cfg, sbp, wl, torch, np):
     actually granted."""
     iters = 2000
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    scratch = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    scratch = torch.zeros((16 << 20) + (3 << 29), dtype=torch.uint8, device="cuda")   # 16 MiB + 1.5 GiB: what modes 7 and 8 walk
+    scratch.random_(0, 256)
     flop = cus * 8.0 * iters * 32 * (2 * 16 * 16 * 32)
     kernels, best = {}, 0.0
-    for mode, name in ((0, "mfma_only"), (3, "mfma_only_32x32x16"), (1, "lockstep_reads"), (2, "pingpong_reads"), (4, "pingpong_12_reads"), (5, "pingpong_8_reads")):
+    for mode, name in ((0, "mfma_only"), (3, "mfma_only_32x32x16"), (1, "lockstep_reads"), (2, "pingpong_reads"), (4, "pingpong_12_reads"), (5, "pingpong_8_reads"), (6, "pingpong_12_reads_l2_operand_stream"),
+                       (7, "pingpong_12_reads_operand_stream_quarter_from_hbm"), (8, "pingpong_12_reads_operand_stream_and_stores")):
         for zero, zname in ((0, "random"), (1, "zeros")):
             ms, n, sclk = sustained(torch, lambda: sbp.sbp_probe_mfma(mode, iters, zero, scratch), 1.5, 100)
             cyc = scratch[:64].cpu().view(torch.int64).numpy()

@@ -278,9 +278,12 @@ int32_t sbp_set_knob(int32_t knob, int32_t value);
  *   mode 0: matrix instructions only; 1: with 16 LDS fragment reads per round interleaved in both waves of a
  *   SIMD and a barrier per round (lockstep schedule); 2: the two waves of a SIMD alternating between their
  *   reads and their matrix instructions (ping-pong schedule); 3: as 0 with 16 v_mfma_f32_32x32x16_bf16 per
- *   round (same flop); 4, 5: as 2 with 12 and with 8 fragment reads per round.
+ *   round (same flop); 4, 5: as 2 with 12 and with 8 fragment reads per round; 6: as 4 plus an operand stream
+ *   of 32 KB per compute unit and round from (L2-resident) global memory straight into LDS; 7: as 6 with 8 of
+ *   those 32 KB from a 1 GiB region that misses every cache; 8: as 7 plus 4 KB of streaming stores per compute
+ *   unit and round.
  *   zero_operands != 0: all-zero fragments instead of pseudo-random ones (no operand toggling).
- *   scratch: 1 MiB of device memory, 16-byte aligned, caller-owned; after the call has completed its first
+ *   scratch: 1 MiB of device memory (mode 6: 16 MiB; modes 7, 8: 16 MiB + 1.5 GiB), 16-byte aligned, caller-owned; after the call has completed its first
  *   8 uint64 words hold the shader cycles each wave of workgroup 0 spent in the loop.
  * Total flop of a call: compute units * 8 * iters * 32 * 16384. */
 int32_t sbp_probe_mfma(int32_t mode, int32_t iters, int32_t zero_operands, void* scratch, void* stream);

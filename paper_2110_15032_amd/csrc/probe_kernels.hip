@@ -13,6 +13,13 @@
 //                                                              (the schedule of gemm_pingpong_kernel)
 //   mode 3  as mode 0 with v_mfma_f32_32x32x16_bf16 (16 instructions of twice the work per round)
 //   mode 4, 5  as mode 2 with 12 and with 8 fragment reads per round: what the fragment traffic costs
+//   mode 6  as mode 4 (12 reads) plus the GEMM's operand stream: every wave brings 4 KB per round from global memory
+//           straight into LDS (32 KB per compute unit and round, its own 32 KB of `scratch`, so the loads hit in L2
+//           after the first round): what the path L2 -> LDS costs on top
+//   mode 7  as mode 6 with one of every wave's four loads taken from a 1 GiB region walked so that it misses every
+//           cache (8 KB per compute unit and round from HBM: about what the GEMMs of the MLP block fetch)
+//   mode 8  as mode 7 plus 4 KB per compute unit and round of streaming stores over a 512 MiB region (about what the
+//           fp32 partials of GEMM2 write)
 // zero != 0 fills the fragments with zeros instead of pseudo-random bf16 values of magnitude 1: same instructions,
 // no operand toggling; the chip's power management then grants a higher clock.
 #include "sbp_internal.h"
@@ -28,10 +35,36 @@ constexpr int PROBE_SLOTS = 6144;   // 16-byte fragments per lane-row in LDS: 96
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int MODE, int NRD = 16>
-__global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cycles, float* sink, int iters, int zero) {
+typedef __attribute__((address_space(1))) char gbl_char;
+
+template <int MODE, int NRD = 16, int STREAM = 0>
+__global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cycles, float* sink, int iters, int zero, char* operands) {
     __shared__ bf16x8 lds[PROBE_SLOTS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // STREAM: this workgroup's 32 KB of operands (filled here, read back round after round into the upper 32 KB of LDS,
+    // which nothing reads)
+    [[maybe_unused]] gbl_char* mine = nullptr;
+    [[maybe_unused]] uint32_t lds_dst = 0;
+    [[maybe_unused]] int wv_stream = 0;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    if constexpr (STREAM > 0) {
+        char* region = operands + (size_t)blockIdx.x * 32768;
+        for (int i = threadIdx.x; i < 2048; i += 512) {
+            u32x4 w;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t h = (uint32_t)(i * 4 + d) * 2654435761u + 0x85EBCA6Bu * (blockIdx.x + 7);
+                h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+                w[d] = zero ? 0u : ((h & 0x807F807Fu) | 0x3F803F80u);
+            }
+            reinterpret_cast<u32x4*>(region)[i] = w;
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0): the fill is in L2 before it is read back
+        const int wv = __builtin_amdgcn_readfirstlane(wave);   // uniform: the load takes a scalar base
+        wv_stream = wv;
+        mine = (gbl_char*)(region + wv * 4096);
+        lds_dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)((char*)lds + 65536 + wv * 4096);
+    }
     for (int i = threadIdx.x; i < PROBE_SLOTS; i += 512) {
         u32x4 w;
 #pragma unroll
@@ -93,6 +126,29 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cyc
                     if (8 * s + i < NRD) fa[s][i] = lds[lane + 64 * ((i + it + 16 * s) & 63)];
                     if (8 * s + 4 + i < NRD) fb[s][i] = lds[lane + 64 * ((i + it + 7 + 16 * s) & 63)];
                 }
+            if constexpr (STREAM > 0) {
+                // four 1 KB loads per wave, global -> LDS, lane i's 16 bytes to base + 16 i; the previous round's
+                // memory operations may still be in flight
+                constexpr int NHIT = STREAM >= 2 ? 3 : 4;
+#pragma unroll
+                for (int q = 0; q < NHIT; ++q)
+                    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                                 : : "v"((uint32_t)(lane * 16 + q * 1024)), "s"(mine), "s"(lds_dst + q * 1024) : "memory", "m0");
+                if constexpr (STREAM >= 2) {
+                    // slot of this workgroup and round in the far regions: 131072 slots, every one touched again only
+                    // after the whole region has passed through the caches
+                    const uint32_t slot = (blockIdx.x * 8191u + (uint32_t)it) & 131071u;
+                    gbl_char* far = (gbl_char*)(operands + (15u << 20) + (size_t)slot * 8192 + wv_stream * 1024);
+                    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                                 : : "v"((uint32_t)(lane * 16)), "s"(far), "s"(lds_dst + 3 * 1024) : "memory", "m0");
+                    if constexpr (STREAM >= 3) {
+                        gbl_char* out = (gbl_char*)(operands + (15u << 20) + ((size_t)1 << 30) + (size_t)slot * 4096 + wv_stream * 512);
+                        const u32x2 v = {(uint32_t)it, (uint32_t)lane};
+                        asm volatile("global_store_dwordx2 %0, %1, %2 nt" : : "v"((uint32_t)(lane * 8)), "v"(v), "s"(out) : "memory");
+                    }
+                }
+                __builtin_amdgcn_s_waitcnt(STREAM >= 3 ? 0x0F75 : 0x0F74);   // vmcnt(5 / 4): one round in flight
+            }
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();
@@ -112,6 +168,7 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cyc
     float s = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    if constexpr (STREAM > 0) __builtin_amdgcn_s_waitcnt(0x0070);   // the last loads land before LDS is released
     sink[blockIdx.x * 512 + threadIdx.x] = s;                   // keeps the matrix instructions alive
     if (blockIdx.x == 0 && lane == 0) cycles[wave] = t1 - t0;
 }
@@ -122,12 +179,19 @@ int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scrat
     const int grid = compute_units();
     unsigned long long* cycles = static_cast<unsigned long long*>(scratch);
     float* sink = reinterpret_cast<float*>(static_cast<char*>(scratch) + 64);
-    if (mode == 0) hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
-    else if (mode == 1) hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
-    else if (mode == 2) hipLaunchKernelGGL(probe_mfma_kernel<2>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
-    else if (mode == 3) hipLaunchKernelGGL(probe_mfma_kernel<3>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
-    else if (mode == 4) hipLaunchKernelGGL((probe_mfma_kernel<2, 12>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
-    else hipLaunchKernelGGL((probe_mfma_kernel<2, 8>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero);
+    // modes 6-8: 32 KB per workgroup behind the first MiB (15 MiB hold 480 such regions), then (modes 7, 8) 1 GiB that
+    // is only read and 512 MiB that are only written
+    char* operands = static_cast<char*>(scratch) + (1 << 20);
+    if (mode >= 6 && grid > 480) return SBP_ERR_UNSUPPORTED;
+    if (mode == 0) hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 1) hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 2) hipLaunchKernelGGL(probe_mfma_kernel<2>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 3) hipLaunchKernelGGL(probe_mfma_kernel<3>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 4) hipLaunchKernelGGL((probe_mfma_kernel<2, 12>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 5) hipLaunchKernelGGL((probe_mfma_kernel<2, 8>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 6) hipLaunchKernelGGL((probe_mfma_kernel<2, 12, 1>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else if (mode == 7) hipLaunchKernelGGL((probe_mfma_kernel<2, 12, 2>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
+    else hipLaunchKernelGGL((probe_mfma_kernel<2, 12, 3>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
     return launch_status(__func__);
 }
 

@@ -136,7 +136,7 @@ const char* sbp_strerror(int32_t status) {
 int32_t sbp_probe_mfma(int32_t mode, int32_t iters, int32_t zero_operands, void* scratch, void* stream) {
     if (!scratch) return SBP_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(scratch) & 15u) return SBP_ERR_ALIGN;
-    if (mode < 0 || mode > 5 || iters < 1 || iters > (1 << 24)) return SBP_ERR_UNSUPPORTED;
+    if (mode < 0 || mode > 8 || iters < 1 || iters > (1 << 24)) return SBP_ERR_UNSUPPORTED;
     return launch_probe_mfma(mode, iters, zero_operands ? 1 : 0, scratch, static_cast<hipStream_t>(stream));
 }
 
