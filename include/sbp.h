@@ -288,6 +288,21 @@ int32_t sbp_set_knob(int32_t knob, int32_t value);
  * Total flop of a call: compute units * 8 * iters * 32 * 16384. */
 int32_t sbp_probe_mfma(int32_t mode, int32_t iters, int32_t zero_operands, void* scratch, void* stream);
 
+/* sbp_probe_mfma for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels, modes 0 to 6, with the staging memory of mode 6 in a
+ * static device array inside the library (15 MiB per device the library runs on, held until the process ends)
+ * instead of a caller workspace.  The call allocates nothing, neither itself nor through the runtime calls it
+ * makes (on its first call on a device it asks the runtime for the array's address and keeps it).
+ *   out: 1 MiB of device memory, 16-byte aligned, caller-owned: 8 uint64 words (shader cycles of the waves of
+ *        workgroup 0), then from byte 64 one float per thread of the grid (compute units * 512): the sum of the
+ *        thread's accumulators, a pure function of (mode, iters, zero_operands) and equal, bit for bit, to what
+ *        sbp_probe_mfma leaves at the same place of its scratch.
+ * SBP_ERR_UNSUPPORTED: modes 7 and 8 (they walk 1.5 GiB), iters outside 1 .. 2^24, or a device with more than
+ * 480 compute units (32 KB of the array each); nothing is launched then.
+ * All calls on one device share that device's array and keep no state in it between calls (mode 6 fills the part
+ * it reads before reading it); calls that overlap in time on one device race on it. */
+int32_t sbp_probe_mfma_static(int32_t mode, int32_t iters, int32_t zero_operands, void* out, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* sbp_strerror(int32_t status);
 

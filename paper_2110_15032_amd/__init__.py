@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     SbpError, SbpTensor, lib, lib_path,
     sbp_infer_matmul, sbp_local_shape, sbp_matmul, sbp_matmul_ex, sbp_matmul_rowmax, sbp_boxing, sbp_boxing_across, sbp_boxing_cast,
     sbp_infer_matmul_2d, sbp_local_shape_2d, sbp_matmul_2d, sbp_boxing_2d,
-    sbp_row_max, sbp_row_sumexp, sbp_xent_loss, sbp_xent_grad, sbp_set_knob, sbp_probe_mfma, sbp_strerror, EXPORTS,
+    sbp_row_max, sbp_row_sumexp, sbp_xent_loss, sbp_xent_grad, sbp_set_knob, sbp_probe_mfma, sbp_probe_mfma_static, sbp_strerror, EXPORTS,
 )

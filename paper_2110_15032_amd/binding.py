@@ -31,7 +31,7 @@ KNOB_BOX_REDUCE = 2
 #: every symbol include/sbp.h declares
 EXPORTS = ("sbp_infer_matmul", "sbp_local_shape", "sbp_matmul", "sbp_matmul_ex", "sbp_matmul_rowmax", "sbp_boxing", "sbp_boxing_across", "sbp_boxing_cast",
            "sbp_infer_matmul_2d", "sbp_local_shape_2d", "sbp_matmul_2d", "sbp_boxing_2d",
-           "sbp_row_max", "sbp_row_sumexp", "sbp_xent_loss", "sbp_xent_grad", "sbp_set_knob", "sbp_probe_mfma", "sbp_strerror")
+           "sbp_row_max", "sbp_row_sumexp", "sbp_xent_loss", "sbp_xent_grad", "sbp_set_knob", "sbp_probe_mfma", "sbp_probe_mfma_static", "sbp_strerror")
 
 
 class _CTensor(ctypes.Structure):
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.sbp_xent_grad.argtypes = [T, i32, T, T, T, T, T, i32, vp]
         L.sbp_set_knob.argtypes = [i32, i32]
         L.sbp_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
+        L.sbp_probe_mfma_static.argtypes = [i32, i32, i32, vp, vp]
         L.sbp_strerror.argtypes = [i32]
         L.sbp_strerror.restype = ctypes.c_char_p
         for f in EXPORTS[:-1]:
@@ -249,6 +250,11 @@ def sbp_xent_grad(logits: SbpTensor, sbp_l: int, labels: SbpTensor, gmax: SbpTen
 def sbp_probe_mfma(mode: int, iters: int, zero_operands: int, scratch, stream=None) -> None:
     ptr = scratch if isinstance(scratch, int) else scratch.data_ptr()
     _check(lib().sbp_probe_mfma(mode, iters, zero_operands, ctypes.c_void_p(ptr), _stream_ptr(stream)), "sbp_probe_mfma")
+
+
+def sbp_probe_mfma_static(mode: int, iters: int, zero_operands: int, out, stream=None) -> None:
+    ptr = out if isinstance(out, int) else out.data_ptr()
+    _check(lib().sbp_probe_mfma_static(mode, iters, zero_operands, ctypes.c_void_p(ptr), _stream_ptr(stream)), "sbp_probe_mfma_static")
 
 
 def sbp_set_knob(knob: int, value: int) -> None:

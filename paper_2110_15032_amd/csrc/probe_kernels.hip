@@ -22,6 +22,9 @@
 //           fp32 partials of GEMM2 write)
 // zero != 0 fills the fragments with zeros instead of pseudo-random bf16 values of magnitude 1: same instructions,
 // no operand toggling; the chip's power management then grants a higher clock.
+#include <atomic>
+#include <cstdio>
+
 #include "sbp_internal.h"
 
 namespace sbp {
@@ -175,14 +178,17 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(unsigned long long* cyc
 
 }  // namespace
 
-int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scratch, hipStream_t st) {
-    const int grid = compute_units();
-    unsigned long long* cycles = static_cast<unsigned long long*>(scratch);
-    float* sink = reinterpret_cast<float*>(static_cast<char*>(scratch) + 64);
-    // modes 6-8: 32 KB per workgroup behind the first MiB (15 MiB hold 480 such regions), then (modes 7, 8) 1 GiB that
-    // is only read and 512 MiB that are only written
-    char* operands = static_cast<char*>(scratch) + (1 << 20);
-    if (mode >= 6 && grid > 480) return SBP_ERR_UNSUPPORTED;
+// Staging memory of sbp_probe_mfma_static (mode 6: 32 KB of operands per workgroup), held by every device the
+// library runs on until the process ends.  In host code this name is only a handle for hipGetSymbolAddress:
+// the device address it yields (per device) is what the kernels are given.
+constexpr size_t PROBE_STATIC_BYTES = (size_t)15 << 20;
+}  // namespace sbp
+static __device__ __align__(256) unsigned char scratch[sbp::PROBE_STATIC_BYTES];
+namespace sbp {
+
+namespace {
+// cycles: 8 uint64; sink: one float per thread of the grid; operands: staging of the modes 6-8 (see the kernel)
+int32_t launch_probe(int32_t mode, int32_t iters, int32_t zero, unsigned long long* cycles, float* sink, char* operands, int grid, hipStream_t st) {
     if (mode == 0) hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
     else if (mode == 1) hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
     else if (mode == 2) hipLaunchKernelGGL(probe_mfma_kernel<2>, dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
@@ -193,6 +199,44 @@ int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scrat
     else if (mode == 7) hipLaunchKernelGGL((probe_mfma_kernel<2, 12, 2>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
     else hipLaunchKernelGGL((probe_mfma_kernel<2, 12, 3>), dim3(grid), dim3(512), 0, st, cycles, sink, iters, zero, operands);
     return launch_status(__func__);
+}
+}  // namespace
+
+int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scratch_arg, hipStream_t st) {
+    const int grid = compute_units();
+    unsigned long long* cycles = static_cast<unsigned long long*>(scratch_arg);
+    float* sink = reinterpret_cast<float*>(static_cast<char*>(scratch_arg) + 64);
+    // modes 6-8: 32 KB per workgroup behind the first MiB (15 MiB hold 480 such regions), then (modes 7, 8) 1 GiB that
+    // is only read and 512 MiB that are only written
+    char* operands = static_cast<char*>(scratch_arg) + (1 << 20);
+    if (mode >= 6 && grid > 480) return SBP_ERR_UNSUPPORTED;
+    return launch_probe(mode, iters, zero, cycles, sink, operands, grid, st);
+}
+
+// The same kernels with the staging memory in the library's own static device array: nothing is allocated, here
+// or in the runtime calls made (the address of the array is asked of the runtime once per device and kept).
+int32_t launch_probe_mfma_static(int32_t mode, int32_t iters, int32_t zero, void* out, hipStream_t st) {
+    constexpr int MAX_DEV = 64;
+    static std::atomic<char*> base[MAX_DEV];   // device address of `scratch` on every device, null = not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return SBP_ERR_LAUNCH;
+    char* ptr = base[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // of the current device's copy
+        if (e != hipSuccess || !p) {
+            fprintf(stderr, "libsbp_mi355x: hipGetSymbolAddress(scratch) failed: %s\n", hipGetErrorString(e));
+            return SBP_ERR_LAUNCH;
+        }
+        ptr = static_cast<char*>(p);
+        base[dev].store(ptr, std::memory_order_release);   // two threads racing here store the same address
+    }
+    const int grid = compute_units();
+    // mode 6 stages 32 KB per workgroup; more workgroups than the array holds are refused, never truncated
+    if ((size_t)grid * 32768 > PROBE_STATIC_BYTES || (size_t)grid * 512 * sizeof(float) + 64 > ((size_t)1 << 20)) return SBP_ERR_UNSUPPORTED;
+    unsigned long long* cycles = static_cast<unsigned long long*>(out);
+    float* sink = reinterpret_cast<float*>(static_cast<char*>(out) + 64);
+    return launch_probe(mode, iters, zero, cycles, sink, ptr, grid, st);
 }
 
 }  // namespace sbp

@@ -140,6 +140,14 @@ int32_t sbp_probe_mfma(int32_t mode, int32_t iters, int32_t zero_operands, void*
     return launch_probe_mfma(mode, iters, zero_operands ? 1 : 0, scratch, static_cast<hipStream_t>(stream));
 }
 
+int32_t sbp_probe_mfma_static(int32_t mode, int32_t iters, int32_t zero_operands, void* out, void* stream) {
+    if (!out) return SBP_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(out) & 15u) return SBP_ERR_ALIGN;
+    // modes 7 and 8 walk 1.5 GiB of caller memory: beyond what the library's own array holds
+    if (mode < 0 || mode > 6 || iters < 1 || iters > (1 << 24)) return SBP_ERR_UNSUPPORTED;
+    return launch_probe_mfma_static(mode, iters, zero_operands ? 1 : 0, out, static_cast<hipStream_t>(stream));
+}
+
 int32_t sbp_set_knob(int32_t knob, int32_t value) {
     if (knob == SBP_KNOB_GEMM_VARIANT && value >= 0 && value < 64) {
         g_gemm_variant.store(value);

@@ -84,6 +84,8 @@ int32_t launch_gemm_pingpong(const GemmPlan& plan, int max_m, int max_n, int ord
 int compute_units();
 // Diagnostic matrix-pipe loop (probe_kernels.hip); scratch: 1 MiB of device memory.
 int32_t launch_probe_mfma(int32_t mode, int32_t iters, int32_t zero, void* scratch, hipStream_t stream);
+// The same with the staging memory in a static device array of the library (modes 0-6); out: 1 MiB.
+int32_t launch_probe_mfma_static(int32_t mode, int32_t iters, int32_t zero, void* out, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
 // Row statistics of the model-parallel softmax.
