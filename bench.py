@@ -659,7 +659,10 @@ def bench_vendor_gemm(args, cfg, sbp, wl, torch, np):
     """Diagnostic, not part of the path: the vendor GEMM library (through torch.bmm / torch.matmul, bf16 in, bf16 out)
     on the three GEMM shapes of the workloads and on the unsharded logical products, N(0, 0.02) operands, sustained
     two seconds each with the shader clock sampled.  Context for the hand-written kernels' rate on the same chip;
-    its outputs are bf16 where the path writes fp32 partials, so it moves fewer bytes than the path does."""
+    its outputs are bf16 where the path writes fp32 partials, so it moves fewer bytes than the path does.  The path's
+    own kernels then run on the same operand tensors, timed the same way ("ours_" entries): a like-for-like
+    comparison on one box in one run (the workload benches time the kernels inside their steps instead, between
+    other kernels and on rotating buffers)."""
     g = torch.Generator(device="cuda").manual_seed(1234)
 
     def rnd(*shape):
@@ -677,12 +680,37 @@ def bench_vendor_gemm(args, cfg, sbp, wl, torch, np):
     cases.append(("dp_grad_tn_8x[2048,1024]^T x[2048,4096]", lambda: torch.bmm(xs.transpose(1, 2), dy), 2.0 * 8 * 2048 * 1024 * 4096))
     f, wc = rnd(1024, 512), rnd(8, 512, 125000)
     cases.append(("classifier_8x[1024,512]x[512,125000]", lambda: torch.matmul(f, wc), 2.0 * 8 * 1024 * 512 * 125000))
+    # the path's own kernels on the very same operand tensors, timed the same way in the same run (GEMM1 with and
+    # without its GeLU; GEMM2 and the weight gradient write fp32 partials, the classifier bf16 logits on rows padded to
+    # 128 bytes with the row maximum fused): "ours_" entries
+    def shards(t):
+        return [t[i] for i in range(t.shape[0])]
+
+    k = 8
+    hs = torch.empty(8, 8192, 2048, dtype=torch.bfloat16, device="cuda")
+    y2 = torch.empty(8, 8192, 4096, dtype=torch.float32, device="cuda")
+    dw = torch.empty(8, 1024, 4096, dtype=torch.float32, device="cuda")
+    PL = (125000 + 63) // 64 * 64
+    lg = torch.empty(8, 1024, PL, dtype=torch.bfloat16, device="cuda")
+    mx = torch.empty(8, 1024, 1, dtype=torch.float32, device="cuda")
+    Xb, W1 = sbp.SbpTensor([x] * k, 8192, 4096, sbp.BF16), sbp.SbpTensor(shards(w1), 4096, 16384, sbp.BF16)
+    Hs = sbp.SbpTensor(shards(hs), 8192, 16384, sbp.BF16)
+    H2, W2, Y2 = sbp.SbpTensor(shards(h), 8192, 16384, sbp.BF16), sbp.SbpTensor(shards(w2), 16384, 4096, sbp.BF16), sbp.SbpTensor(shards(y2), 8192, 4096, sbp.F32)
+    XT, DY, DW = sbp.SbpTensor(shards(xs), 1024, 16384, sbp.BF16, 1), sbp.SbpTensor(shards(dy), 16384, 4096, sbp.BF16), sbp.SbpTensor(shards(dw), 1024, 4096, sbp.F32)
+    Fc, Wc = sbp.SbpTensor([f] * k, 1024, 512, sbp.BF16), sbp.SbpTensor(shards(wc), 512, 1000000, sbp.BF16)
+    Lg, Mx = sbp.SbpTensor(shards(lg), 1024, 1000000, sbp.BF16, 0, PL), sbp.SbpTensor(shards(mx), 1024, 1, sbp.F32)
+    ours = [("ours_mlp_gemm1_no_epilogue", lambda: sbp.sbp_matmul(Xb, sbp.B, W1, sbp.S(1), Hs, sbp.S(1), k), cases[0][2]),
+            ("ours_mlp_gemm1_gelu", lambda: sbp.sbp_matmul_ex(Xb, sbp.B, W1, sbp.S(1), Hs, sbp.S(1), k, None, sbp.EPI_GELU), cases[0][2]),
+            ("ours_mlp_gemm2_fp32_partials", lambda: sbp.sbp_matmul(H2, sbp.S(1), W2, sbp.S(0), Y2, sbp.P_SUM, k), cases[1][2]),
+            ("ours_dp_grad_tn_fp32_partials", lambda: sbp.sbp_matmul(XT, sbp.S(1), DY, sbp.S(0), DW, sbp.P_SUM, k), cases[4][2]),
+            ("ours_classifier_rowmax_padded_rows", lambda: sbp.sbp_matmul_rowmax(Fc, sbp.B, Wc, sbp.S(1), Lg, sbp.S(1), Mx, k), cases[5][2])]
     kernels, best = {}, 0.0
-    for name, call, flop in cases:
+    for name, call, flop in cases + ours:
         ms, n, sclk = sustained(torch, call, 2.0, 50)
         tf = flop / ms / 1e9
         kernels[name] = {"ms": round(ms, 4), "tflops": round(tf, 1), "sclk_mhz_smi": sclk, "calls": n}
-        best = max(best, tf)
+        if not name.startswith("ours_"):
+            best = max(best, tf)
     roof = {"bound": "mfma", "kernel": "vendor library GEMM through torch (bf16 out), best shape", "achieved": round(best, 1),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(best / PEAK_BF16_TFLOPS, 4), "traffic": None}
     return result_line(args, "diagnostic: vendor-library bf16 GEMM (torch.matmul / torch.bmm) on the workloads' GEMM shapes, sustained 2 s each",
