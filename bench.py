@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--preroll-ms", type=float, default=100.0,
+                    help="before the warm-up steps, run the step for about this long (wall clock) so that the device has left its "
+                         "idle clocks: after idling (input generation) the part needs some 30 ms of work to reach the clock it "
+                         "then holds, more than a few 2 ms steps; 0 = off.  The timed region is not touched")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="token rows in the oracle's sample")
     ap.add_argument("--variant", type=int, default=0, help="GEMM kernel variant knob (0 = default)")
@@ -83,6 +87,7 @@ def main():
     import workloads as wl
     from workloads import CONFIGS
 
+    PREROLL["ms"] = args.preroll_ms
     sbp.lib()   # fail loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
@@ -150,6 +155,7 @@ def main():
         # Yb -> Y as a B -> B identity: k contiguous copies of 128 MiB, 1 GiB in + 1 GiB out in total
         sbp.sbp_boxing(Yb, sbp.B, Y, sbp.B, k, stream)
         torch.cuda.synchronize()
+    preroll_steps = preroll(torch, step, args.preroll_ms)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -203,6 +209,8 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "preroll_ms": args.preroll_ms,
+        "preroll_steps": preroll_steps,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -264,9 +272,32 @@ def make_arena(torch, np, args, layout=None):
     return arena
 
 
+PREROLL = {"ms": 0.0, "steps": 0}     # set from --preroll-ms in main(); steps: what the last run needed
+
+
+def preroll(torch, step, ms):
+    """Runs step() back to back for about `ms` of wall clock (in batches, synchronised) before any warm-up or timed
+    step: the device leaves its idle clocks.  Returns the number of steps run."""
+    n = 0
+    if ms > 0:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(4):
+                step()
+            n += 4
+            torch.cuda.synchronize()
+    return n
+
+
 def time_stages(torch, stages_of, steps, warmup):
     """stages_of(s) -> list of callables for step s.  Returns (avg ms per stage, wall ms per step)."""
     stream = torch.cuda.current_stream()
+
+    def one_step():
+        for f in stages_of(0):
+            f(stream)
+    PREROLL["steps"] = preroll(torch, one_step, PREROLL["ms"])
     for s in range(warmup):
         for f in stages_of(s):
             f(stream)
@@ -287,6 +318,7 @@ def time_stages(torch, stages_of, steps, warmup):
 def result_line(args, workload, k, value, unit, wall_ms, kernels, roofline, dtype="bf16"):
     return {"metric": f"SBP matmul TFLOP/s (% MFMA peak) + boxing GB/s (% HBM peak), k={k}",
             "value": round(value, 3), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "preroll_ms": PREROLL["ms"], "preroll_steps": PREROLL["steps"],
             "ms_per_step": round(wall_ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": dtype, "data": "synthetic", "config": {"workload": workload, "k": k, "gemm_variant": args.variant},
             "kernels": kernels, "roofline": roofline}
