@@ -36,7 +36,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E peak, GB/s
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the
 # calibration copy; summary in profiles/bench_mlp_k8_counters.md).  Offline figures, not re-measured here.
 TRAFFIC_SOURCE = "constant from an earlier rocprofv3 --pmc run of this command (profiles/bench_mlp_k8_counters.md), not measured by this run"
-TRAFFIC_BYTES = {"gemm1": 1.853e9, "gemm2": 2.713e9, "boxing_p2b": 2.098e9}
+TRAFFIC_BYTES = {"gemm1": 1.853e9, "gemm2": 2.683e9, "boxing_p2b": 2.099e9}
 
 
 def shard_range(n, k, i):
