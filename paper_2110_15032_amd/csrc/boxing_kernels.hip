@@ -48,6 +48,8 @@ struct BoxParams {
     // started for an empty pair (npairs == 0: task t is pair (t / ko, t % ko))
     int32_t npairs;
     uint8_t pair_i[2 * SBP_MAX_K], pair_j[2 * SBP_MAX_K];
+    // reductions only: blockIdx.z = conversion b of a batch, its sources src[b * ki + i], its destinations dst[b * ko + j]
+    int32_t batch;
 };
 
 struct Task {
@@ -150,6 +152,7 @@ template <typename V, int OP, int KS, int UNROLL>
 __global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
     const Task T = make_task(p, blockIdx.y);
     const int32_t ns = KS > 0 ? KS : T.ns;
+    const int32_t sb = (int32_t)blockIdx.z * p.ki, db = (int32_t)blockIdx.z * p.ko;   // this conversion's pointers
     const uint32_t cols_v = (uint32_t)(T.cols / p.vec_elems);
     const uint32_t total = (uint32_t)T.rows * cols_v;
     const int64_t src_ld_v = T.src_ld / p.vec_elems, dst_ld_v = T.dst_ld / p.vec_elems;
@@ -169,18 +172,18 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
                 dpos[u] = dst_off_v + (int64_t)r * dst_ld_v + c;
                 V a;
                 if constexpr (KS > 0) {   // sources 0 .. KS-1
-                    a = __builtin_nontemporal_load(static_cast<const V*>(p.src[0]) + spos);
+                    a = __builtin_nontemporal_load(static_cast<const V*>(p.src[sb]) + spos);
                     V part[KS];
 #pragma unroll
-                    for (int i = 1; i < KS; ++i) part[i] = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos);
+                    for (int i = 1; i < KS; ++i) part[i] = __builtin_nontemporal_load(static_cast<const V*>(p.src[sb + i]) + spos);
 #pragma unroll
                     for (int i = 1; i < KS; ++i) a = combine<OP>(a, part[i]);
                 } else {
                     if constexpr (OP == BOX_SUM) a = V(0.0f);
                     else a = V(-__builtin_inff());
-                    if (ns > 0) a = __builtin_nontemporal_load(static_cast<const V*>(p.src[T.s0]) + spos);
+                    if (ns > 0) a = __builtin_nontemporal_load(static_cast<const V*>(p.src[sb + T.s0]) + spos);
                     for (int i = 1; i < ns; ++i) {
-                        const V b = __builtin_nontemporal_load(static_cast<const V*>(p.src[T.s0 + i * T.sstep]) + spos);
+                        const V b = __builtin_nontemporal_load(static_cast<const V*>(p.src[sb + T.s0 + i * T.sstep]) + spos);
                         a = combine<OP>(a, b);
                     }
                 }
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const uint32_t idx = base + u * stride;
-                if (idx < total) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[T.d0 + j]) + dpos[u]);
+                if (idx < total) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[db + T.d0 + j]) + dpos[u]);
             }
         }
     }
@@ -205,6 +208,7 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_kernel(BoxParams p) {
 template <typename V, int OP, int KS>
 __global__ __launch_bounds__(BOX_THREADS) void box_reduce_diag_kernel(BoxParams p) {
     const Task T = make_task(p, blockIdx.y);
+    const int32_t sb = (int32_t)blockIdx.z * p.ki, db = (int32_t)blockIdx.z * p.ko;   // this conversion's pointers
     const uint32_t cols_v = (uint32_t)(T.cols / p.vec_elems);
     const uint32_t total = (uint32_t)T.rows * cols_v;
     const int64_t src_ld_v = T.src_ld / p.vec_elems, dst_ld_v = T.dst_ld / p.vec_elems;
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_diag_kernel(BoxParams 
             for (int u = 0; u < KS; ++u) {
                 const int i = s - u;
                 if (i < 0 || i >= KS) continue;
-                const V v = __builtin_nontemporal_load(static_cast<const V*>(p.src[i]) + spos[u]);
+                const V v = __builtin_nontemporal_load(static_cast<const V*>(p.src[sb + i]) + spos[u]);
                 acc[u] = i == 0 ? v : combine<OP>(acc[u], v);
             }
         }
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(BOX_THREADS) void box_reduce_diag_kernel(BoxParams 
 #pragma unroll
             for (int u = 0; u < KS; ++u) {
                 const uint32_t idx = base + u * BOX_THREADS;
-                if (idx < total) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[T.d0 + j]) + dpos[u]);
+                if (idx < total) __builtin_nontemporal_store(acc[u], static_cast<V*>(p.dst[db + T.d0 + j]) + dpos[u]);
             }
         }
     }
@@ -592,10 +596,14 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     const int32_t ki = plan.k, ko = plan.k_out;
     p.axis_in = (plan.sbp_in == SBP_S(0) || plan.sbp_in == SBP_S(1)) ? plan.sbp_in : -1;
     p.axis_out = (plan.sbp_out == SBP_S(0) || plan.sbp_out == SBP_S(1)) ? plan.sbp_out : -1;
-    for (int i = 0; i < ki; ++i) p.src[i] = plan.src[i];
-    for (int i = 0; i < ko; ++i) p.dst[i] = plan.dst[i];
     const bool p_in = plan.sbp_in == SBP_P_SUM || plan.sbp_in == SBP_P_MAX;
     const bool p_out = plan.sbp_out == SBP_P_SUM || plan.sbp_out == SBP_P_MAX;
+    const int32_t nb = plan.batch > 1 ? plan.batch : 1;
+    // a batch: reductions only (their kernels take the conversion from blockIdx.z)
+    if (nb > 1 && (!p_in || (plan.sbp_in == plan.sbp_out && ki == ko) || (int64_t)nb * (ki > ko ? ki : ko) > SBP_MAX_K)) return SBP_ERR_UNSUPPORTED;
+    p.batch = nb;
+    for (int i = 0; i < nb * ki; ++i) p.src[i] = plan.src[i];
+    for (int i = 0; i < nb * ko; ++i) p.dst[i] = plan.dst[i];
     int32_t tasks;
     if (plan.sbp_in == plan.sbp_out && ki == ko) {
         p.mode = M_IDENT;
@@ -728,7 +736,7 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     // 1 / 4 MiB: 13 / 16 us against 7.6 / 11 with four vectors per lane; 16 MiB: 45 against 49).
     int unroll = 1;
     if (reduce && vbytes == 16) {
-        const int64_t all_units = max_units * tasks;
+        const int64_t all_units = max_units * tasks * nb;
         const bool medium = all_units > ((int64_t)1 << 19) && all_units <= ((int64_t)1 << 21);
         const bool diag = p.mode != M_P2P && (p.ki == 4 || p.ki == 8 || p.ki == 16);
         unroll = medium ? (diag ? 16 : 8) : 4;
@@ -742,10 +750,10 @@ int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream) {
     // again.  Reductions issue k loads per vector and are indifferent between 32768 and 65536.
     const int64_t cap_total = reduce ? 65536 : 32768;
     int64_t bx = (max_units + (int64_t)BOX_THREADS * per_lane - 1) / ((int64_t)BOX_THREADS * per_lane);
-    const int64_t cap = (cap_total + tasks - 1) / tasks;
+    const int64_t cap = (cap_total + (int64_t)tasks * nb - 1) / ((int64_t)tasks * nb);
     if (bx > cap) bx = cap;
     if (bx < 1) bx = 1;
-    const dim3 grid((uint32_t)bx, (uint32_t)tasks);
+    const dim3 grid((uint32_t)bx, (uint32_t)tasks, (uint32_t)nb);
 
     if (reduce) {
         if (plan.sbp_in == SBP_P_SUM) launch_reduce<BOX_SUM>(p, grid, unroll, stream);

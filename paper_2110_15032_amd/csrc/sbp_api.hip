@@ -513,11 +513,34 @@ int32_t sbp_boxing_2d(const sbp_tensor_t* in, const sbp_t* s_in, const sbp_tenso
         tout[g] = {&pout[(size_t)g * kk], l.rows, l.cols, out->dtype, 0};
     }
     const sbp_t a = inner ? s_in[1] : s_in[0], b = inner ? s_out[1] : s_out[0];
-    for (int pass = 0; pass < 2; ++pass)   // validate every part, then launch every part
-        for (int32_t g = 0; g < parts; ++g) {
-            if (tin[g].rows * tin[g].cols == 0) continue;
-            if ((st = boxing_impl(&tin[g], a, kk, &tout[g], b, kk, stream, pass == 1)) != SBP_OK) return st;
+    for (int32_t g = 0; g < parts; ++g) {   // validate every part before anything is enqueued
+        if (tin[g].rows * tin[g].cols == 0) continue;
+        if ((st = boxing_impl(&tin[g], a, kk, &tout[g], b, kk, stream, false)) != SBP_OK) return st;
+    }
+    // Reductions of equally shaped parts go out as ONE launch (pin and pout already hold the pointers part by part):
+    // two half-size kernels one after the other leave the memory system idle at the seam.
+    bool same = parts > 1 && is_partial(a) && tin[0].rows * tin[0].cols > 0;
+    for (int32_t g = 1; g < parts && same; ++g) same = tin[g].rows == tin[0].rows && tin[g].cols == tin[0].cols;
+    if (same) {
+        BoxPlan plan{};
+        plan.rows = tin[0].rows;
+        plan.cols = tin[0].cols;
+        plan.k = plan.k_out = kk;
+        plan.sbp_in = a;
+        plan.sbp_out = b;
+        plan.elem_bytes = elem_bytes(in->dtype);
+        plan.batch = parts;
+        for (size_t i = 0; i < pin.size(); ++i) {
+            plan.src[i] = pin[i];
+            plan.dst[i] = pout[i];
         }
+        st = launch_boxing(plan, static_cast<hipStream_t>(stream));
+        if (st != SBP_ERR_UNSUPPORTED) return st;   // unsupported as a batch: nothing was enqueued, go part by part
+    }
+    for (int32_t g = 0; g < parts; ++g) {
+        if (tin[g].rows * tin[g].cols == 0) continue;
+        if ((st = boxing_impl(&tin[g], a, kk, &tout[g], b, kk, stream, true)) != SBP_OK) return st;
+    }
     return SBP_OK;
 }
 

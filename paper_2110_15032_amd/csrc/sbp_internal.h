@@ -43,6 +43,11 @@ struct BoxPlan {
     int32_t k_out;            // devices holding the output (= k on one device set; launch_boxing_cast ignores it)
     int32_t sbp_in, sbp_out;  // sbp_t values
     int32_t elem_bytes;       // 2 or 4
+    // batch > 1: that many independent conversions of equal shape and signature in one launch (the groups of a
+    // device grid): conversion b reads src[b * k + i] and writes dst[b * k_out + j]; batch * max(k, k_out) <=
+    // SBP_MAX_K.  Only reductions (P input) take it; launch_boxing returns SBP_ERR_UNSUPPORTED, before anything is
+    // enqueued, for any other conversion, and the caller then launches the conversions one by one.
+    int32_t batch;
 };
 
 int32_t launch_boxing(const BoxPlan& plan, hipStream_t stream);
