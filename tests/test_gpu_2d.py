@@ -220,3 +220,58 @@ def test_table3_row2_then_all_reduce_inside_every_group():
         for b in range(k1):
             assert_matmul_close(got[a * k1 + b], block, 2e-2, f"group {a} device {b}")
             assert_bits_equal(got[a * k1 + b], got[a * k1], "copies inside a group")
+
+
+@pytest.mark.parametrize("k0,k1", [(2, 4), (4, 2), (3, 5)])
+@pytest.mark.parametrize("pm", ["sum", "max"])
+def test_group_reductions_in_one_launch_equal_one_boxing_per_group(k0, k1, pm):
+    """Reductions of equally shaped groups leave sbp_boxing_2d as ONE launch (the group in the grid's third
+    dimension); uneven groups go one by one.  Either way every group's result must be, bit for bit, what
+    sbp_boxing gives for that group alone (same kernels, same shard order), and match the oracle.  Sizes span
+    many workgroups, even and uneven group shapes, inner and outer conversions, both partial operations."""
+    PX = P if pm == "sum" else orc.P_MAX
+    cases = [((S0, PX), (S0, B)), ((S0, PX), (S0, S1)), ((PX, S1), (B, S1)), ((PX, B), (S0, B)), ((B, PX), (B, S0))]
+    for n, shape in enumerate([(k0 * 96, k1 * 256), (k0 * 96 + 1, k1 * 256 + 8)]):
+        for c, (si, so) in enumerate(cases):
+            T = rnd_f32(300 + 10 * n + c, shape)
+            rng = np.random.default_rng(1000 + 10 * n + c)
+            ins = []
+            if pm == "sum":
+                ins = scatter2_random(400 + 10 * n + c, T, si, k0, k1)
+            else:
+                # random locals; the tensor they stand for is whatever the oracle assembles
+                for a in range(k0):
+                    for b in range(k1):
+                        ins.append(rng.standard_normal(orc.local_shape2(*shape, si, k0, k1, a, b)).astype(np.float32))
+                if si[0] == B:      # every group holds the same tensor
+                    ins = [ins[b].copy() for _ in range(k0) for b in range(k1)]
+                if si[1] == B:      # the devices of a group hold copies
+                    ins = [ins[a * k1].copy() for a in range(k0) for _ in range(k1)]
+            ref = orc.boxing2(ins, si, so, k0, k1)
+            d_in = Dev2.from_host(ins, *shape)
+            d_out = Dev2.empty(*shape, np.float32, so, k0, k1)
+            sbp.sbp_boxing_2d(d_in.desc, abi2(si), d_out.desc, abi2(so), k0, k1)
+            sync()
+            got = d_out.host()
+            for i, (g, r) in enumerate(zip(got, ref)):
+                assert g.shape == r.shape
+                if pm == "max":
+                    assert np.array_equal(g.astype(np.float64), np.asarray(r, dtype=np.float64)), f"{si}->{so} device {i}"
+                else:
+                    assert np.allclose(g, r, rtol=0, atol=1e-5 * (1 + np.abs(r).max())), f"{si}->{so} device {i}"
+            # the same conversion group by group through the 1-D entry point
+            inner = si[0] == so[0]
+            parts, kk = (k0, k1) if inner else (k1, k0)
+            keep = si[0] if inner else si[1]
+            a1, b1 = (si[1], so[1]) if inner else (si[0], so[0])
+            for g in range(parts):
+                devs = [g * k1 + i if inner else i * k1 + g for i in range(kk)]
+                lr, lc = orc.local_shape(*shape, keep, parts, g) if keep in (S0, S1) else shape
+                if lr * lc == 0:
+                    continue
+                t_in = sbp.SbpTensor([d_in.dev[d] for d in devs], lr, lc, sbp.F32)
+                outs = [empty_dev(got[d].shape, np.float32) for d in devs]
+                sbp.sbp_boxing(t_in, TO_ABI[a1], sbp.SbpTensor(outs, lr, lc, sbp.F32), TO_ABI[b1], kk)
+                sync()
+                for d, o in zip(devs, outs):
+                    assert_bits_equal(got[d], download(o, np.dtype(np.float32)).reshape(got[d].shape), f"{si}->{so} group {g} device {d}")
