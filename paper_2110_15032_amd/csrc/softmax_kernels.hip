@@ -147,14 +147,16 @@ __global__ __launch_bounds__(RS_THREADS) void xent_grad_kernel(XentPlan p) {
         const int64_t pos = (int64_t)r * p.ld[i] + c, opos = (int64_t)r * p.ld_out[i] + c;
         float v[VE];
         if constexpr (BF16 && VE == 8) {
-            const u32x4 w = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.logits[i]) + pos);
+            // streaming load: the gradient pass is the last reader of the logits (measured 2 % faster than a cached load;
+            // two items per lane and round, both loaded before either is worked on, 1 % slower than this)
+            const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.logits[i]) + pos));
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 v[2 * d] = bf16_lo(w[d]);
                 v[2 * d + 1] = bf16_hi(w[d]);
             }
         } else if constexpr (!BF16 && VE == 4) {
-            const f32x4 w = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.logits[i]) + pos);
+            const f32x4 w = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(static_cast<const float*>(p.logits[i]) + pos));
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = w[e];
         } else {
