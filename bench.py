@@ -8,7 +8,9 @@ devices as 8 shard sets in one GPU's HBM):
     Y  = H W2           W2 [16384,4096] bf16 S(0)                         -> Y P(sum), 8 fp32 partials
     Yb = boxing(Y)      P(sum) -> B (all-reduce): 8 partials -> 8 identical fp32 copies
 
-Inputs are seeded synthetic tensors, resident in HBM before the timed region.  Prints ONE JSON line.
+Inputs are seeded synthetic tensors, resident in HBM before the timed region.  Before the warm-up steps the step
+runs for --preroll-ms (default 100 ms, reported as "preroll_ms" / "preroll_steps") so that the device has left its
+idle clocks; then exactly --warmup untimed and --steps timed steps.  Prints ONE JSON line.
 `value` is the matmul work of a step (2.199 TFLOP) divided by the time of the whole step (boxing
 included); the per-kernel figures are in "kernels", "roofline" (dominant kernel) and
 "roofline_boxing".  The CPU oracle is timed on a bounded sample of the same workload.
