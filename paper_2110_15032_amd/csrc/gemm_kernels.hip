@@ -1387,10 +1387,15 @@ __global__ __launch_bounds__(HW * 2, HW == 256 ? 4 : 2) void gemm_split_kernel(G
             stash(CUR ? sF0 : sF1);
             // Scheduling hint: the vector instructions that split the next stage's fp32 values go a few behind each of
             // this stage's matrix instructions instead of in a block after them (the matrix pipe runs an instruction
-            // for 16 cycles while the wave may issue others): 0.68 -> 0.64 ms on the late product of the U V W chain.
-            static_for<3 * FM * FN>([&](auto) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          // 1 MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 2 * TF::PER_THREAD, 0);         // vector ALU
+            // for 16 cycles while the wave may issue others).  Which matrix instructions take them is by measurement
+            // (ms on [4096,4096] x [4096,1024] per device, 8 devices; no hint / behind all 48 / behind the last 32,
+            // i.e. not the first term's): fp32 A, wide tile .673 / .645 / .606, narrow .784 / .791 / .735;
+            // fp32 B, wide .736 / .687 / .749, narrow .862 / .866 / .833.
+            constexpr int FIRST = (F32_B && HW == 256) ? 0 : FM * FN;
+            constexpr int PER = ((F32_B && HW == 256) ? 2 : 3) * TF::PER_THREAD;
+            static_for<3 * FM * FN>([&](auto i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                             // 1 MFMA
+                if constexpr (decltype(i)::value >= FIRST) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);   // vector ALU
             });
         }
         __builtin_amdgcn_s_waitcnt(0x0070);   // this wave's direct-to-LDS loads have landed
